@@ -1,0 +1,263 @@
+"""Pins for the CPU oracle (no GPU).  The paper (arXiv 2404.09526) prints no numeric attention
+example, so the oracle is pinned by: a second dense brute-force routine, a library attention
+routine on a special case, closed forms, permutation / partition invariance (the token-pool and
+scale-up/scale-down properties of Sec. 4 and Sec. 6), and the KV-bytes figure of Sec. 1 / Sec. 4.1."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2404_09526_amd import workloads as wl
+
+D = 128
+
+
+def rand_bits(rng, shape, scale=1.0):
+    x = torch.from_numpy((rng.standard_normal(shape) * scale).astype(np.float32)).to(torch.bfloat16)
+    return wl.bits(x)
+
+
+def make(rng, Tq, Tkv, Hq, Hkv, d=D, pos_range=None):
+    q = rand_bits(rng, (Tq, Hq, d))
+    k = rand_bits(rng, (Tkv, Hkv, d))
+    v = rand_bits(rng, (Tkv, Hkv, d))
+    hi = pos_range or (Tq + Tkv)
+    allpos = rng.permutation(hi)[: Tq + Tkv].astype(np.int32)
+    return q, k, v, allpos[:Tq].copy(), allpos[Tq:].copy()
+
+
+# ------------------------------------------------------------------ P1: brute force on tiny inputs
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("Hq,Hkv", [(1, 1), (4, 4), (4, 2), (4, 1)])
+@pytest.mark.parametrize("d", [128, 16])
+def test_matches_dense_brute_force(causal, Hq, Hkv, d):
+    rng = np.random.default_rng(10 + Hq * 7 + Hkv + d)
+    q, k, v, qp, kp = make(rng, 23, 61, Hq, Hkv, d)
+    qp[3] = kp.min() - 1                                           # a row that sees no key
+    scale = 1.0 / math.sqrt(d)
+    O, L = oracle.partial_attn_all(q, k, v, qp, kp, scale, causal)
+    Ob, Lb = oracle.brute_force_attention(q, k, v, qp, kp, scale, causal)
+    if causal:
+        assert np.isinf(Lb).any() and not np.isinf(Lb).all()   # the case has empty visible sets
+    assert np.array_equal(np.isinf(L), np.isinf(Lb))
+    fin = ~np.isinf(Lb)
+    np.testing.assert_allclose(L[fin], Lb[fin], rtol=0, atol=1e-12)
+    np.testing.assert_allclose(O, Ob, rtol=0, atol=1e-12)
+    assert (O[~fin] == 0).all()
+
+
+# ------------------------------------------------------------------ P2: library routine on a special case
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (8, 2)])
+def test_matches_torch_sdpa_contiguous_causal(Hq, Hkv):
+    rng = np.random.default_rng(3)
+    Tq, n = 40, 96
+    q = rand_bits(rng, (Tq, Hq, D)); k = rand_bits(rng, (n, Hkv, D)); v = rand_bits(rng, (n, Hkv, D))
+    kp = np.arange(n, dtype=np.int32)
+    qp = (n - Tq + np.arange(Tq)).astype(np.int32)
+    scale = 1.0 / math.sqrt(D)
+    O, L = oracle.partial_attn_all(q, k, v, qp, kp, scale, True)
+    tq = torch.from_numpy(oracle.bf16_bits_to_f64(q)).permute(1, 0, 2)          # [Hq,Tq,D]
+    G = Hq // Hkv
+    tk = torch.from_numpy(oracle.bf16_bits_to_f64(k)).permute(1, 0, 2).repeat_interleave(G, 0)
+    tv = torch.from_numpy(oracle.bf16_bits_to_f64(v)).permute(1, 0, 2).repeat_interleave(G, 0)
+    mask = torch.from_numpy(kp[None, :] <= qp[:, None])
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask, scale=scale)
+    np.testing.assert_allclose(O, ref.permute(1, 0, 2).numpy(), rtol=0, atol=1e-12)
+    scores = scale * tq @ tk.transpose(1, 2)
+    scores = scores.masked_fill(~mask, float("-inf"))
+    np.testing.assert_allclose(L, torch.logsumexp(scores, -1).T.numpy(), rtol=0, atol=1e-12)
+
+
+# ------------------------------------------------------------------ P3: closed forms
+def test_closed_forms():
+    rng = np.random.default_rng(5)
+    Tq, n, H = 7, 50, 2
+    q, k, v, qp, kp = make(rng, Tq, n, H, H)
+    scale = 0.3
+    qf, kf, vf = (oracle.bf16_bits_to_f64(a) for a in (q, k, v))
+    vis = kp[None, :] <= qp[:, None]                                  # [Tq, n]
+    nvis = vis.sum(1)
+    # all keys identical -> uniform weights over the visible set
+    k_same = np.broadcast_to(k[:1], k.shape).copy()
+    O, L = oracle.partial_attn_all(q, k_same, v, qp, kp, scale, True)
+    s = scale * np.einsum("thd,hd->th", qf, kf[0])
+    for t in range(Tq):
+        if nvis[t] == 0:
+            assert np.isinf(L[t]).all() and (O[t] == 0).all()
+        else:
+            np.testing.assert_allclose(L[t], s[t] + math.log(nvis[t]), atol=1e-12)
+            np.testing.assert_allclose(O[t], vf[vis[t]].mean(0), atol=1e-12)
+    # q = 0 -> LSE = ln(n), O = mean V (non-causal)
+    O, L = oracle.partial_attn_all(np.zeros_like(q), k, v, qp, kp, scale, False)
+    np.testing.assert_allclose(L, math.log(n), atol=1e-12)
+    np.testing.assert_allclose(O, np.broadcast_to(vf.mean(0), O.shape), atol=1e-12)
+    # exactly one visible key -> O = v, LSE = its score
+    kp1 = np.full(n, 10**6, np.int32); kp1[17] = 0
+    O, L = oracle.partial_attn_all(q, k, v, np.abs(qp), kp1, scale, True)
+    np.testing.assert_allclose(O, np.broadcast_to(vf[17], O.shape), atol=1e-12)
+    np.testing.assert_allclose(L, scale * np.einsum("thd,hd->th", qf, kf[17]), atol=1e-12)
+    # constant V -> O is that constant
+    vc = np.broadcast_to(v[:1], v.shape).copy()
+    O, _ = oracle.partial_attn_all(q, k, vc, qp, kp, scale, False)
+    np.testing.assert_allclose(O, np.broadcast_to(vf[0], O.shape), atol=1e-12)
+    # empty visible set
+    O, L = oracle.partial_attn_all(q, k, v, np.full(Tq, -1, np.int32), kp, scale, True)
+    assert np.isneginf(L).all() and (O == 0).all()
+    # the scale is applied to the scores (a wrong/missing scale changes LSE for one key)
+    O, L2 = oracle.partial_attn_all(q, k[17:18], v[17:18], qp, kp[17:18], 2 * scale, False)
+    np.testing.assert_allclose(L2, 2 * scale * np.einsum("thd,hd->th", qf, kf[17]), atol=1e-12)
+
+
+def test_mask_is_inclusive_and_uses_global_positions():
+    rng = np.random.default_rng(6)
+    q, k, v, _, _ = make(rng, 1, 3, 1, 1)
+    kp = np.array([5, 9, 7], np.int32)
+    vf = oracle.bf16_bits_to_f64(v)
+    for qpos, expect in [(4, []), (5, [0]), (7, [0, 2]), (8, [0, 2]), (9, [0, 1, 2])]:
+        O, L = oracle.partial_attn_all(q, k, v, np.array([qpos], np.int32), kp, 0.0, True)
+        if not expect:
+            assert np.isneginf(L).all()
+        else:   # scale 0 -> uniform over exactly the visible rows
+            np.testing.assert_allclose(L, math.log(len(expect)), atol=1e-13)
+            np.testing.assert_allclose(O[0, 0], vf[expect, 0].mean(0), atol=1e-13)
+
+
+# ------------------------------------------------------------------ P4: permutation invariance (token pool)
+def test_token_order_inside_a_shard_is_irrelevant():
+    rng = np.random.default_rng(7)
+    q, k, v, qp, kp = make(rng, 9, 77, 4, 2)
+    O, L = oracle.partial_attn_all(q, k, v, qp, kp, 0.1, True)
+    perm = rng.permutation(77)
+    O2, L2 = oracle.partial_attn_all(q, k[perm], v[perm], qp, kp[perm], 0.1, True)
+    np.testing.assert_allclose(O2, O, atol=1e-12)
+    fin = ~np.isinf(L)
+    assert np.array_equal(np.isinf(L2), np.isinf(L))
+    np.testing.assert_allclose(L2[fin], L[fin], atol=1e-12)
+
+
+# ------------------------------------------------------------------ P5: GQA head mapping
+def test_gqa_equals_mha_on_repeated_kv_heads():
+    rng = np.random.default_rng(8)
+    q, k, v, qp, kp = make(rng, 11, 40, 8, 2)
+    O, L = oracle.partial_attn_all(q, k, v, qp, kp, 0.09, True)
+    kr, vr = np.repeat(k, 4, axis=1), np.repeat(v, 4, axis=1)        # head h <- kv head h // 4
+    O2, L2 = oracle.partial_attn_all(q, kr, vr, qp, kp, 0.09, True)
+    np.testing.assert_array_equal(O2, O)
+    np.testing.assert_array_equal(L2, L)
+    # and distinct KV heads really give distinct results (mapping is not h % Hkv)
+    assert not np.allclose(O[:, 1], oracle.partial_attn_all(q, np.tile(k, (1, 4, 1)), np.tile(v, (1, 4, 1)),
+                                                           qp, kp, 0.09, True)[0][:, 1])
+
+
+# ------------------------------------------------------------------ P6-P8: merge
+def _partition(rng, n, parts, kind):
+    if kind == "contiguous":
+        cuts = np.sort(rng.integers(0, n + 1, parts - 1))
+        edges = np.concatenate([[0], cuts, [n]])
+        return [np.arange(edges[i], edges[i + 1]) for i in range(parts)]
+    if kind == "striped":
+        return [np.arange(i, n, parts) for i in range(parts)]
+    lab = rng.integers(0, parts, n)
+    lab[lab == parts - 1] = 0 if parts > 1 else 0                   # leave the last part empty
+    return [np.nonzero(lab == i)[0] for i in range(parts)]
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("kind", ["contiguous", "striped", "random"])
+@pytest.mark.parametrize("parts", [1, 2, 3, 8])
+def test_merge_over_any_partition_equals_unpartitioned(causal, kind, parts):
+    rng = np.random.default_rng(100 + parts)
+    q, k, v, qp, kp = make(rng, 13, 90, 4, 2)
+    O, L = oracle.partial_attn_all(q, k, v, qp, kp, 0.11, causal)
+    Os, Ls = [], []
+    for idx in _partition(rng, 90, parts, kind):
+        o, l = oracle.partial_attn_all(q, k[idx], v[idx], qp, kp[idx], 0.11, causal)
+        Os.append(o); Ls.append(l)
+    Om, Lm = oracle.merge_partials(np.stack(Os), np.stack(Ls))
+    assert np.array_equal(np.isinf(Lm), np.isinf(L))
+    fin = ~np.isinf(L)
+    np.testing.assert_allclose(Lm[fin], L[fin], atol=1e-12)
+    np.testing.assert_allclose(Om, O, atol=1e-12)
+    assert not np.isnan(Om).any()
+
+
+def test_merge_algebra():
+    rng = np.random.default_rng(9)
+    O = rng.standard_normal((3, 5, 2, 16)); L = rng.standard_normal((3, 5, 2)) * 3
+    Oab, Lab = oracle.merge_partials(O[:2], L[:2])
+    O1, L1 = oracle.merge_partials(np.stack([Oab, O[2]]), np.stack([Lab, L[2]]))
+    O2, L2 = oracle.merge_partials(O, L)
+    np.testing.assert_allclose(O1, O2, atol=1e-13); np.testing.assert_allclose(L1, L2, atol=1e-13)
+    O3, L3 = oracle.merge_partials(O[::-1], L[::-1])                 # commutative
+    np.testing.assert_allclose(O3, O2, atol=1e-13); np.testing.assert_allclose(L3, L2, atol=1e-13)
+    Oi, Li = oracle.merge_partials(O[:1], L[:1])                     # P = 1 is the identity
+    np.testing.assert_array_equal(Oi, O[0]); np.testing.assert_array_equal(Li, L[0])
+    Lz = np.concatenate([L, np.full((1, 5, 2), -np.inf)]); Oz = np.concatenate([O, rng.standard_normal((1, 5, 2, 16))])
+    O4, L4 = oracle.merge_partials(Oz, Lz)                           # a -inf partial changes nothing
+    np.testing.assert_array_equal(O4, O2); np.testing.assert_array_equal(L4, L2)
+    O5, L5 = oracle.merge_partials(Oz[3:], Lz[3:])                   # all -inf
+    assert np.isneginf(L5).all() and (O5 == 0).all()
+    # two-partial closed form: weights sigmoid(L0 - L1)
+    w = 1 / (1 + np.exp(L[1] - L[0]))
+    Oc, Lc = oracle.merge_partials(O[:2], L[:2])
+    np.testing.assert_allclose(Oc, w[..., None] * O[0] + (1 - w[..., None]) * O[1], atol=1e-13)
+    np.testing.assert_allclose(Lc, np.logaddexp(L[0], L[1]), atol=1e-13)
+
+
+# ------------------------------------------------------------------ P9: decode = partial attention on the gathered rows
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (8, 2)])
+def test_decode_equals_partial_attention_on_gathered_rows(Hq, Hkv):
+    rng = np.random.default_rng(11)
+    S, lens = 257, [0, 1, 40, 97]
+    B = len(lens)
+    kpool = rand_bits(rng, (S, Hkv, D)); vpool = rand_bits(rng, (S, Hkv, D))
+    q = rand_bits(rng, (B, Hq, D))
+    slots = rng.permutation(S)[: sum(lens)].astype(np.int32)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    O, L = oracle.partial_attn_decode_all(q, kpool, vpool, slots, off, 0.2)
+    for b in range(B):
+        sl = slots[off[b]:off[b + 1]]
+        if len(sl) == 0:
+            assert np.isneginf(L[b]).all() and (O[b] == 0).all()
+            continue
+        o, l = oracle.partial_attn_all(q[b:b + 1], kpool[sl], vpool[sl], np.zeros(1, np.int32),
+                                       np.zeros(len(sl), np.int32), 0.2, False)
+        np.testing.assert_allclose(O[b], o[0], atol=1e-13); np.testing.assert_allclose(L[b], l[0], atol=1e-13)
+        ob, lb = oracle.brute_force_attention(q[b:b + 1], kpool[sl], vpool[sl], None, None, 0.2, False)
+        np.testing.assert_allclose(O[b], ob[0], atol=1e-12); np.testing.assert_allclose(L[b], lb[0], atol=1e-12)
+
+
+# ------------------------------------------------------------------ P10: append / gather exactness
+def test_append_is_an_exact_scatter():
+    rng = np.random.default_rng(12)
+    S, T, row = 300, 50, (2, 16)
+    kp0 = rng.integers(0, 65536, (S,) + row).astype(np.uint16); vp0 = rng.integers(0, 65536, (S,) + row).astype(np.uint16)
+    k = rng.integers(0, 65536, (T,) + row).astype(np.uint16); v = rng.integers(0, 65536, (T,) + row).astype(np.uint16)
+    slots = rng.permutation(S)[:T].astype(np.int32)
+    slots[::7] = -1
+    kp, vp = kp0.copy(), vp0.copy()
+    oracle.kv_append(k, v, slots, kp, vp)
+    kept = slots >= 0
+    np.testing.assert_array_equal(kp[slots[kept]], k[kept]); np.testing.assert_array_equal(vp[slots[kept]], v[kept])
+    untouched = np.setdiff1d(np.arange(S), slots[kept])
+    np.testing.assert_array_equal(kp[untouched], kp0[untouched]); np.testing.assert_array_equal(vp[untouched], vp0[untouched])
+    assert len(untouched) == S - kept.sum()
+    with pytest.raises(ValueError):
+        oracle.kv_append(k[:1], v[:1], np.array([S], np.int32), kp, vp)
+
+
+# ------------------------------------------------------------------ P11: bytes per token (Sec. 1, Sec. 4.1)
+def test_kv_bytes_per_token_matches_the_papers_488GB():
+    layers, Hkv, d = 32, 32, 128          # LWM-1M-Text = Llama-2-7B shape (Sec. 7.1)
+    per_token_layer = 2 * Hkv * d * 2     # K and V rows, 2 bytes each
+    assert per_token_layer == 16384
+    total = per_token_layer * layers * 10**6
+    assert abs(total / 2**30 - 488.28125) < 1e-6      # "exceeds 488GB" for a 1M-token request
+
+
+def test_bf16_conversion_is_exact():
+    vals = torch.tensor([0.0, -0.0, 1.0, -2.5, 3.140625, 2.0**-126, 2.0**-133, 65280.0, float("inf")])
+    b = wl.bits(vals.to(torch.bfloat16))
+    np.testing.assert_array_equal(oracle.bf16_bits_to_f64(b), vals.to(torch.bfloat16).to(torch.float64).numpy())
