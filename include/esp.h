@@ -1,0 +1,152 @@
+/*
+ * esp.h -- C ABI of libesp: one GPU's share of elastic-sequence-parallel (ESP)
+ * attention on AMD MI355X (gfx950), after LoongServe (arXiv 2404.09526).
+ *
+ * The library computes, with hand-written HIP kernels only (there is no CPU or
+ * library fallback):
+ *   esp_partial_attn_prefill  a causal query chunk against ONE local KV shard
+ *   esp_partial_attn_decode   one query token per request against the KV rows
+ *                             this instance holds in its token-granular pool
+ *   esp_merge_partials        log-sum-exp combination of partial results
+ *   esp_kv_append             scatter of K/V rows into scheduler-chosen slots
+ *
+ * Conventions common to all calls
+ *   - Every data pointer is DEVICE memory owned by the caller unless a
+ *     parameter says "host".  The library never allocates, frees or keeps
+ *     device memory and holds no state between calls.
+ *   - bf16 tensors are passed as `const void*` (16-bit patterns); layouts are
+ *     token-major and dense: Q/O [T, Hq, D], K/V [T, Hkv, D], pools
+ *     [S, Hkv, D] (one for K, one for V), LSE [T, Hq] float.
+ *   - Query head h reads KV head h / (Hq / Hkv).  D must be 128.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Work is enqueued asynchronously; the library never synchronises.
+ *   - Results are deterministic: the same inputs give the same bits.
+ *   - Return value: ESP_OK or a negative esp_status; nothing is enqueued when
+ *     an error is returned, except for ESP_ERR_HIP where the launch itself
+ *     failed.  esp_last_error() gives a thread-local message.
+ *   - The CONTENT of device index arrays (positions, offsets, slots) is
+ *     trusted, as it comes from the scheduler (scaling plan, Sec. 3 and 4.1):
+ *     out-of-range or duplicate slots are undefined behaviour.
+ *   - A row with no visible key yields O = 0 and LSE = -inf, never NaN.
+ *   - LSE is the natural logarithm of the sum of exp(softmax_scale * q.k)
+ *     over the visible keys.
+ */
+#ifndef ESP_H_
+#define ESP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t esp_status;
+#define ESP_OK                0
+#define ESP_ERR_INVALID_ARG  (-1) /* null pointer, negative size, Hq % Hkv != 0, P out of range */
+#define ESP_ERR_UNSUPPORTED  (-2) /* D != 128, or a head count the kernels do not cover        */
+#define ESP_ERR_WORKSPACE    (-3) /* workspace missing or smaller than the matching *_bytes()  */
+#define ESP_ERR_HIP          (-4) /* a HIP launch failed; see esp_last_error()                 */
+
+#define ESP_MAX_PARTIALS 16
+
+/*
+ * Prefill partial attention (Sec. 2.3, Fig. 1: instance i attends its local
+ * queries q_i to a key-value segment kv_j; kernel remarks in Sec. 6).
+ *
+ * For every local query row t and head h: softmax attention over the rows of
+ * ONE KV shard that belong to the same request, restricted (causal != 0) to
+ * rows with kv_pos <= q_pos[t] on GLOBAL token positions, so that contiguous,
+ * striped or arbitrary sequence-parallel layouts use the same call.  Emits the
+ * un-merged output O (bf16, normalised within the shard) and LSE (float).
+ *
+ *   q [Tq,Hq,D], k/v [Tkv,Hkv,D] bf16; q_pos [Tq], kv_pos [Tkv] int32.
+ *   cu_q, cu_kv: int32 [batch+1] prefix offsets of the requests packed in q and
+ *     in the shard (request r owns rows cu[r]..cu[r+1]); both NULL with
+ *     batch = 1 means one request spanning everything.
+ *   max_q, max_kv: upper bounds on a request's row counts (host-known; used
+ *     only to size the launch).
+ *   O [Tq,Hq,D] bf16, LSE [Tq,Hq] float: written for every row.
+ *   workspace: at least esp_prefill_workspace_bytes(...) bytes, 256-byte
+ *     aligned; contents need not be preserved or initialised.
+ * Positions may be in any order; ascending order inside a request lets whole
+ * tiles be skipped or left unmasked.
+ */
+esp_status esp_partial_attn_prefill(
+    const void* q, const void* k, const void* v,
+    const int32_t* q_pos, const int32_t* kv_pos,
+    const int32_t* cu_q, const int32_t* cu_kv, int32_t batch,
+    int32_t Tq, int32_t Tkv, int32_t max_q, int32_t max_kv,
+    int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale, int32_t causal,
+    void* O, float* LSE,
+    void* workspace, size_t workspace_bytes, void* stream);
+
+size_t esp_prefill_workspace_bytes(int32_t Tq, int32_t Tkv, int32_t batch,
+                                   int32_t Hq, int32_t Hkv, int32_t D);
+
+/*
+ * Decode partial attention (Sec. 4.2, Fig. 8: every instance of the group runs
+ * the local attention of the batch's query tokens against the key-value rows it
+ * holds; token-granular pool of Sec. 6).
+ *
+ * Request b attends its single query token to the pool rows
+ * slot_idx[seq_offsets[b] .. seq_offsets[b+1]) (no mask: all resident tokens
+ * precede the query).  A request with no resident row gives O = 0, LSE = -inf.
+ *
+ *   q [B,Hq,D] bf16; k_pool/v_pool [num_slots,Hkv,D] bf16;
+ *   slot_idx int32 [total_tokens]; seq_offsets int32 [B+1], seq_offsets[0] = 0,
+ *   seq_offsets[B] = total_tokens; max_len >= every request's length.
+ *   O [B,Hq,D] bf16, LSE [B,Hq] float.
+ *   workspace: at least esp_decode_workspace_bytes(...) bytes, 256-byte aligned.
+ */
+esp_status esp_partial_attn_decode(
+    const void* q, const void* k_pool, const void* v_pool, int64_t num_slots,
+    const int32_t* slot_idx, const int32_t* seq_offsets, int32_t B,
+    int32_t total_tokens, int32_t max_len,
+    int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale,
+    void* O, float* LSE,
+    void* workspace, size_t workspace_bytes, void* stream);
+
+size_t esp_decode_workspace_bytes(int32_t B, int32_t total_tokens, int32_t max_len,
+                                  int32_t Hq, int32_t Hkv, int32_t D);
+
+/*
+ * Combination of partial results ("generate the final output", Sec. 2.3;
+ * results "sent back to the master", Sec. 4.2).  For each (token, head):
+ *   m = max_p LSE_p,  w_p = exp(LSE_p - m),
+ *   O = sum_p w_p O_p / sum_p w_p,   LSE = m + ln sum_p w_p.
+ * Partials with LSE = -inf weigh 0; all -inf gives O = 0, LSE = -inf.
+ *
+ *   O_parts, LSE_parts: HOST arrays of P device pointers (1 <= P <=
+ *     ESP_MAX_PARTIALS) to bf16 [T,Hq,D] and float [T,Hq]; read before return.
+ *   O [T,Hq,D] bf16; LSE_out [T,Hq] float or NULL.  O may alias O_parts[i].
+ */
+esp_status esp_merge_partials(
+    const void* const* O_parts, const float* const* LSE_parts, int32_t P,
+    int32_t T, int32_t Hq, int32_t D,
+    void* O, float* LSE_out, void* stream);
+
+/*
+ * KV append / selective retention (Sec. 4.1, Fig. 7: instances of the new
+ * group save selected key-value rows into their pool at the places the scaling
+ * plan names; Sec. 4.2: a master saves the new token's K/V into its pool).
+ *   k_pool[slot_idx[t]] = k[t], v_pool[slot_idx[t]] = v[t] for slot_idx[t] >= 0;
+ *   rows with a negative slot are not kept.  A pure copy of 16-bit patterns.
+ *
+ *   k, v [T,Hkv,D] bf16; slot_idx int32 [T]; pools [num_slots,Hkv,D] bf16.
+ */
+esp_status esp_kv_append(
+    const void* k, const void* v, const int32_t* slot_idx, int32_t T,
+    void* k_pool, void* v_pool, int64_t num_slots, int32_t Hkv, int32_t D,
+    void* stream);
+
+/* Message of the last error on the calling thread (static storage, never NULL). */
+const char* esp_last_error(void);
+
+/* Library version string, e.g. "esp 0.1 gfx950". */
+const char* esp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ESP_H_ */

@@ -1,0 +1,203 @@
+"""ctypes binding of libesp.so: same names as the C ABI (include/esp.h), argument marshalling only.
+
+PyTorch provides device memory and the current stream; every step of the path runs in the
+library's HIP kernels.  Importing this module fails loudly if the library is missing: there is
+no CPU or PyTorch fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libesp.so")
+
+ESP_OK, ESP_ERR_INVALID_ARG, ESP_ERR_UNSUPPORTED, ESP_ERR_WORKSPACE, ESP_ERR_HIP = 0, -1, -2, -3, -4
+ESP_MAX_PARTIALS = 16
+
+EXPORTS = (
+    "esp_partial_attn_prefill", "esp_prefill_workspace_bytes", "esp_partial_attn_decode",
+    "esp_decode_workspace_bytes", "esp_merge_partials", "esp_kv_append", "esp_last_error", "esp_version",
+)
+
+
+class EspError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"libesp status {status}: {message}")
+        self.status = status
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'` "
+            "(hipcc --offload-arch=gfx950).  There is no fallback path.")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+    L.esp_partial_attn_prefill.argtypes = [vp] * 7 + [i32] * 8 + [f32, i32, vp, vp, vp, sz, vp]
+    L.esp_partial_attn_prefill.restype = i32
+    L.esp_prefill_workspace_bytes.argtypes = [i32] * 6
+    L.esp_prefill_workspace_bytes.restype = sz
+    L.esp_partial_attn_decode.argtypes = [vp, vp, vp, i64, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, vp, vp, sz, vp]
+    L.esp_partial_attn_decode.restype = i32
+    L.esp_decode_workspace_bytes.argtypes = [i32] * 6
+    L.esp_decode_workspace_bytes.restype = sz
+    L.esp_merge_partials.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp]
+    L.esp_merge_partials.restype = i32
+    L.esp_kv_append.argtypes = [vp, vp, vp, i32, vp, vp, i64, i32, i32, vp]
+    L.esp_kv_append.restype = i32
+    L.esp_last_error.argtypes = []
+    L.esp_last_error.restype = ctypes.c_char_p
+    L.esp_version.argtypes = []
+    L.esp_version.restype = ctypes.c_char_p
+    return L
+
+
+lib = _load()
+
+
+def last_error() -> str:
+    return lib.esp_last_error().decode()
+
+
+def version() -> str:
+    return lib.esp_version().decode()
+
+
+def _check(status: int) -> None:
+    if status != ESP_OK:
+        raise EspError(status, last_error())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> torch.Tensor:
+    if not t.is_cuda:
+        raise ValueError(f"{name}: must live in device memory")
+    if t.dtype != dtype:
+        raise ValueError(f"{name}: expected {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: must be contiguous")
+    return t
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def esp_prefill_workspace_bytes(Tq, Tkv, batch, Hq, Hkv, D) -> int:
+    return int(lib.esp_prefill_workspace_bytes(Tq, Tkv, batch, Hq, Hkv, D))
+
+
+def esp_decode_workspace_bytes(B, total_tokens, max_len, Hq, Hkv, D) -> int:
+    return int(lib.esp_decode_workspace_bytes(B, total_tokens, max_len, Hq, Hkv, D))
+
+
+def esp_partial_attn_prefill(q, k, v, q_pos, kv_pos, cu_q=None, cu_kv=None, max_q=None, max_kv=None,
+                             softmax_scale=None, causal=True, O=None, LSE=None, workspace=None):
+    """q [Tq,Hq,D], k/v [Tkv,Hkv,D] bf16; q_pos/kv_pos int32; cu_q/cu_kv int32 [batch+1] or None.
+    Returns (O bf16 [Tq,Hq,D], LSE fp32 [Tq,Hq]) of attention against this one KV shard."""
+    _dev(q, torch.bfloat16, "q"); _dev(k, torch.bfloat16, "k"); _dev(v, torch.bfloat16, "v")
+    _dev(q_pos, torch.int32, "q_pos"); _dev(kv_pos, torch.int32, "kv_pos")
+    Tq, Hq, D = q.shape
+    Tkv, Hkv, Dk = k.shape
+    if v.shape != k.shape or Dk != D or q_pos.shape != (Tq,) or kv_pos.shape != (Tkv,):
+        raise ValueError("prefill: shape mismatch")
+    batch = 1
+    if cu_q is not None:
+        _dev(cu_q, torch.int32, "cu_q"); _dev(cu_kv, torch.int32, "cu_kv")
+        batch = cu_q.numel() - 1
+        if cu_kv.numel() != batch + 1:
+            raise ValueError("prefill: cu_q and cu_kv differ in length")
+        if max_q is None or max_kv is None:
+            raise ValueError("prefill: max_q and max_kv are required with cu_q/cu_kv")
+    else:
+        max_q, max_kv = Tq, Tkv
+    if softmax_scale is None:
+        softmax_scale = D ** -0.5
+    if O is None:
+        O = torch.empty_like(q)
+    if LSE is None:
+        LSE = torch.empty((Tq, Hq), dtype=torch.float32, device=q.device)
+    _dev(O, torch.bfloat16, "O"); _dev(LSE, torch.float32, "LSE")
+    if O.shape != q.shape or LSE.shape != (Tq, Hq):
+        raise ValueError("prefill: output shape mismatch")
+    if workspace is None:
+        workspace = _workspace(esp_prefill_workspace_bytes(Tq, Tkv, batch, Hq, Hkv, D), q.device)
+    _check(lib.esp_partial_attn_prefill(_ptr(q), _ptr(k), _ptr(v), _ptr(q_pos), _ptr(kv_pos), _ptr(cu_q), _ptr(cu_kv),
+                                        batch, Tq, Tkv, int(max_q), int(max_kv), Hq, Hkv, D, float(softmax_scale),
+                                        int(bool(causal)), _ptr(O), _ptr(LSE), _ptr(workspace), workspace.numel(),
+                                        _stream()))
+    return O, LSE
+
+
+def esp_partial_attn_decode(q, k_pool, v_pool, slot_idx, seq_offsets, max_len, softmax_scale=None,
+                            O=None, LSE=None, workspace=None):
+    """q [B,Hq,D] bf16, pools [S,Hkv,D] bf16, slot_idx int32 [total], seq_offsets int32 [B+1].
+    Returns (O bf16 [B,Hq,D], LSE fp32 [B,Hq]) of attention against the resident pool rows."""
+    _dev(q, torch.bfloat16, "q"); _dev(k_pool, torch.bfloat16, "k_pool"); _dev(v_pool, torch.bfloat16, "v_pool")
+    _dev(slot_idx, torch.int32, "slot_idx"); _dev(seq_offsets, torch.int32, "seq_offsets")
+    B, Hq, D = q.shape
+    S, Hkv, Dk = k_pool.shape
+    if v_pool.shape != k_pool.shape or Dk != D or seq_offsets.numel() != B + 1:
+        raise ValueError("decode: shape mismatch")
+    total = slot_idx.numel()
+    if softmax_scale is None:
+        softmax_scale = D ** -0.5
+    if O is None:
+        O = torch.empty_like(q)
+    if LSE is None:
+        LSE = torch.empty((B, Hq), dtype=torch.float32, device=q.device)
+    _dev(O, torch.bfloat16, "O"); _dev(LSE, torch.float32, "LSE")
+    if workspace is None:
+        workspace = _workspace(esp_decode_workspace_bytes(B, total, int(max_len), Hq, Hkv, D), q.device)
+    _check(lib.esp_partial_attn_decode(_ptr(q), _ptr(k_pool), _ptr(v_pool), S, _ptr(slot_idx), _ptr(seq_offsets), B,
+                                       total, int(max_len), Hq, Hkv, D, float(softmax_scale), _ptr(O), _ptr(LSE),
+                                       _ptr(workspace), workspace.numel(), _stream()))
+    return O, LSE
+
+
+def esp_merge_partials(O_parts: Sequence[torch.Tensor], LSE_parts: Sequence[torch.Tensor], O=None, LSE=None,
+                       want_lse: bool = True):
+    """Combine P partial results (bf16 [T,Hq,D], fp32 [T,Hq]) into (O bf16, LSE fp32 or None)."""
+    P = len(O_parts)
+    if P != len(LSE_parts):
+        raise ValueError("merge: O_parts and LSE_parts differ in length")
+    if P == 0:
+        raise ValueError("merge: need at least one partial")
+    for i in range(P):
+        _dev(O_parts[i], torch.bfloat16, f"O_parts[{i}]"); _dev(LSE_parts[i], torch.float32, f"LSE_parts[{i}]")
+        if O_parts[i].shape != O_parts[0].shape or LSE_parts[i].shape != O_parts[0].shape[:-1]:
+            raise ValueError("merge: partial shapes differ")
+    *lead, Hq, D = O_parts[0].shape
+    T = 1
+    for s in lead:
+        T *= s
+    if O is None:
+        O = torch.empty_like(O_parts[0])
+    if LSE is None and want_lse:
+        LSE = torch.empty(O_parts[0].shape[:-1], dtype=torch.float32, device=O.device)
+    op = (ctypes.c_void_p * P)(*[t.data_ptr() for t in O_parts])
+    lp = (ctypes.c_void_p * P)(*[t.data_ptr() for t in LSE_parts])
+    _check(lib.esp_merge_partials(op, lp, P, T, Hq, D, _ptr(O), _ptr(LSE), _stream()))
+    return O, LSE
+
+
+def esp_kv_append(k, v, slot_idx, k_pool, v_pool) -> None:
+    """k_pool[slot_idx[t]] = k[t], v_pool[slot_idx[t]] = v[t] for slot_idx[t] >= 0 (in place)."""
+    _dev(k, torch.bfloat16, "k"); _dev(v, torch.bfloat16, "v"); _dev(slot_idx, torch.int32, "slot_idx")
+    _dev(k_pool, torch.bfloat16, "k_pool"); _dev(v_pool, torch.bfloat16, "v_pool")
+    T, Hkv, D = k.shape
+    if v.shape != k.shape or slot_idx.shape != (T,) or k_pool.shape != v_pool.shape or k_pool.shape[1:] != k.shape[1:]:
+        raise ValueError("append: shape mismatch")
+    _check(lib.esp_kv_append(_ptr(k), _ptr(v), _ptr(slot_idx), T, _ptr(k_pool), _ptr(v_pool), k_pool.shape[0], Hkv, D,
+                             _stream()))

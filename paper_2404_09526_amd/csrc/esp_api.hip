@@ -1,0 +1,130 @@
+// C-ABI entry points of libesp: argument validation and dispatch to the kernel launchers.
+// Every step of the hot path runs in the HIP kernels of this library; there is no fallback.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "esp_common.h"
+
+namespace esp {
+
+static thread_local char g_err[512] = "";
+
+esp_status fail(esp_status code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+esp_status check_launch(const char* what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ESP_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    return ESP_OK;
+}
+
+static bool heads_ok(int32_t Hq, int32_t Hkv) { return Hq > 0 && Hkv > 0 && Hq % Hkv == 0; }
+
+}  // namespace esp
+
+using namespace esp;
+
+extern "C" {
+
+const char* esp_last_error(void) { return g_err; }
+const char* esp_version(void) { return "esp 0.1 gfx950"; }
+
+size_t esp_prefill_workspace_bytes(int32_t Tq, int32_t Tkv, int32_t batch, int32_t Hq, int32_t Hkv, int32_t D) {
+    if (Tq < 0 || Tkv < 0 || batch < 1 || !heads_ok(Hq, Hkv) || D != kHeadDim) return 0;
+    return prefill_workspace_bytes(Tq, Tkv, batch, Hq, Hkv);
+}
+
+size_t esp_decode_workspace_bytes(int32_t B, int32_t total_tokens, int32_t max_len, int32_t Hq, int32_t Hkv,
+                                  int32_t D) {
+    (void)max_len;
+    if (B < 0 || total_tokens < 0 || !heads_ok(Hq, Hkv) || D != kHeadDim) return 0;
+    return decode_workspace_bytes(B, total_tokens, Hq, Hkv);
+}
+
+esp_status esp_partial_attn_prefill(const void* q, const void* k, const void* v, const int32_t* q_pos,
+                                    const int32_t* kv_pos, const int32_t* cu_q, const int32_t* cu_kv, int32_t batch,
+                                    int32_t Tq, int32_t Tkv, int32_t max_q, int32_t max_kv, int32_t Hq, int32_t Hkv,
+                                    int32_t D, float softmax_scale, int32_t causal, void* O, float* LSE,
+                                    void* workspace, size_t workspace_bytes, void* stream) {
+    if (Tq < 0 || Tkv < 0 || batch < 1 || max_q < 0 || max_kv < 0)
+        return fail(ESP_ERR_INVALID_ARG, "prefill: negative size or batch < 1");
+    if (!heads_ok(Hq, Hkv)) return fail(ESP_ERR_INVALID_ARG, "prefill: Hq=%d must be a positive multiple of Hkv=%d", Hq, Hkv);
+    if (D != kHeadDim) return fail(ESP_ERR_UNSUPPORTED, "prefill: head_dim %d unsupported (only 128)", D);
+    if (max_q > Tq || max_kv > Tkv) return fail(ESP_ERR_INVALID_ARG, "prefill: max_q/max_kv exceed Tq/Tkv");
+    if ((cu_q == nullptr) != (cu_kv == nullptr)) return fail(ESP_ERR_INVALID_ARG, "prefill: cu_q and cu_kv must both be given or both NULL");
+    if (cu_q == nullptr && batch != 1) return fail(ESP_ERR_INVALID_ARG, "prefill: batch > 1 needs cu_q/cu_kv");
+    if (cu_q == nullptr && (max_q != Tq || max_kv != Tkv))
+        return fail(ESP_ERR_INVALID_ARG, "prefill: without cu_q/cu_kv, max_q/max_kv must equal Tq/Tkv");
+    if (Tq == 0) return ESP_OK;
+    if (!q || !O || !LSE || !q_pos) return fail(ESP_ERR_INVALID_ARG, "prefill: null q/q_pos/O/LSE");
+    if (Tkv > 0 && (!k || !v || !kv_pos)) return fail(ESP_ERR_INVALID_ARG, "prefill: null k/v/kv_pos");
+    if (!(softmax_scale == softmax_scale) || softmax_scale < 0.f) return fail(ESP_ERR_INVALID_ARG, "prefill: bad softmax_scale");
+    size_t need = prefill_workspace_bytes(Tq, Tkv, batch, Hq, Hkv);
+    if (need > 0 && (!workspace || workspace_bytes < need))
+        return fail(ESP_ERR_WORKSPACE, "prefill: workspace needs %zu bytes, got %zu", need, workspace ? workspace_bytes : (size_t)0);
+    if (need > 0 && ((uintptr_t)workspace & 255)) return fail(ESP_ERR_WORKSPACE, "prefill: workspace not 256-byte aligned");
+    return launch_prefill(q, k, v, q_pos, kv_pos, cu_q, cu_kv, batch, Tq, Tkv, max_q, max_kv, Hq, Hkv,
+                          softmax_scale, causal, O, LSE, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+esp_status esp_partial_attn_decode(const void* q, const void* k_pool, const void* v_pool, int64_t num_slots,
+                                   const int32_t* slot_idx, const int32_t* seq_offsets, int32_t B,
+                                   int32_t total_tokens, int32_t max_len, int32_t Hq, int32_t Hkv, int32_t D,
+                                   float softmax_scale, void* O, float* LSE, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
+    if (B < 0 || total_tokens < 0 || max_len < 0 || num_slots < 0)
+        return fail(ESP_ERR_INVALID_ARG, "decode: negative size");
+    if (!heads_ok(Hq, Hkv)) return fail(ESP_ERR_INVALID_ARG, "decode: Hq=%d must be a positive multiple of Hkv=%d", Hq, Hkv);
+    if (D != kHeadDim) return fail(ESP_ERR_UNSUPPORTED, "decode: head_dim %d unsupported (only 128)", D);
+    if (max_len > total_tokens) return fail(ESP_ERR_INVALID_ARG, "decode: max_len exceeds total_tokens");
+    if (B == 0) return ESP_OK;
+    if (!q || !O || !LSE || !seq_offsets) return fail(ESP_ERR_INVALID_ARG, "decode: null q/seq_offsets/O/LSE");
+    if (total_tokens > 0 && (!k_pool || !v_pool || !slot_idx || num_slots == 0))
+        return fail(ESP_ERR_INVALID_ARG, "decode: null pool/slot_idx");
+    if (!(softmax_scale == softmax_scale) || softmax_scale < 0.f) return fail(ESP_ERR_INVALID_ARG, "decode: bad softmax_scale");
+    if (Hkv % 4 != 0 || !(Hkv == 4 || Hkv == 8 || Hkv == 16 || Hkv % 32 == 0))
+        return fail(ESP_ERR_UNSUPPORTED, "decode: Hkv=%d unsupported (4, 8, 16 or a multiple of 32)", Hkv);
+    int G = Hq / Hkv;
+    if (!(G == 1 || G == 2 || G == 4 || G == 8)) return fail(ESP_ERR_UNSUPPORTED, "decode: Hq/Hkv=%d unsupported (1, 2, 4, 8)", G);
+    size_t need = decode_workspace_bytes(B, total_tokens, Hq, Hkv);
+    if (!workspace || workspace_bytes < need)
+        return fail(ESP_ERR_WORKSPACE, "decode: workspace needs %zu bytes, got %zu", need, workspace ? workspace_bytes : (size_t)0);
+    if ((uintptr_t)workspace & 255) return fail(ESP_ERR_WORKSPACE, "decode: workspace not 256-byte aligned");
+    return launch_decode(q, k_pool, v_pool, slot_idx, seq_offsets, B, total_tokens, Hq, Hkv, softmax_scale, O, LSE,
+                         workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+esp_status esp_merge_partials(const void* const* O_parts, const float* const* LSE_parts, int32_t P, int32_t T,
+                              int32_t Hq, int32_t D, void* O, float* LSE_out, void* stream) {
+    if (P < 1 || P > ESP_MAX_PARTIALS) return fail(ESP_ERR_INVALID_ARG, "merge: P=%d outside 1..%d", P, ESP_MAX_PARTIALS);
+    if (T < 0 || Hq <= 0) return fail(ESP_ERR_INVALID_ARG, "merge: negative size");
+    if (D != kHeadDim) return fail(ESP_ERR_UNSUPPORTED, "merge: head_dim %d unsupported (only 128)", D);
+    if (!O_parts || !LSE_parts) return fail(ESP_ERR_INVALID_ARG, "merge: null pointer arrays");
+    if (T == 0) return ESP_OK;
+    if (!O) return fail(ESP_ERR_INVALID_ARG, "merge: null O");
+    MergeArgs a;
+    for (int p = 0; p < P; ++p) {
+        if (!O_parts[p] || !LSE_parts[p]) return fail(ESP_ERR_INVALID_ARG, "merge: partial %d is null", p);
+        a.O_parts[p] = O_parts[p];
+        a.LSE_parts[p] = LSE_parts[p];
+    }
+    for (int p = P; p < ESP_MAX_PARTIALS; ++p) { a.O_parts[p] = nullptr; a.LSE_parts[p] = nullptr; }
+    return launch_merge(a, P, (int64_t)T * Hq, O, LSE_out, (hipStream_t)stream);
+}
+
+esp_status esp_kv_append(const void* k, const void* v, const int32_t* slot_idx, int32_t T, void* k_pool, void* v_pool,
+                         int64_t num_slots, int32_t Hkv, int32_t D, void* stream) {
+    if (T < 0 || num_slots < 0 || Hkv <= 0) return fail(ESP_ERR_INVALID_ARG, "append: negative size");
+    if (D != kHeadDim) return fail(ESP_ERR_UNSUPPORTED, "append: head_dim %d unsupported (only 128)", D);
+    if (T == 0) return ESP_OK;
+    if (!k || !v || !slot_idx || !k_pool || !v_pool) return fail(ESP_ERR_INVALID_ARG, "append: null pointer");
+    if (num_slots == 0) return fail(ESP_ERR_INVALID_ARG, "append: empty pool");
+    return launch_kv_append(k, v, slot_idx, T, k_pool, v_pool, Hkv * D * 2, (hipStream_t)stream);
+}
+
+}  // extern "C"

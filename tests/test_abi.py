@@ -1,0 +1,101 @@
+"""CPU-only checks of the boundary: the library loads, exports every symbol include/esp.h declares, and
+rejects bad arguments on the host before touching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2404_09526_amd import build
+    if build.is_stale():
+        build.build_lib(force=True)
+    from paper_2404_09526_amd import binding
+    return binding
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "esp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(esp_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(lib.EXPORTS)
+    for n in names:
+        assert getattr(lib.lib, n) is not None
+
+
+def test_version_and_error_string(lib):
+    assert "gfx950" in lib.version()
+    assert isinstance(lib.last_error(), str)
+
+
+def test_workspace_queries(lib):
+    assert lib.esp_prefill_workspace_bytes(8192, 8192, 1, 32, 32, 128) >= (8192 // 64) * 8
+    assert lib.esp_prefill_workspace_bytes(8192, 8192, 1, 32, 32, 64) == 0        # unsupported head_dim
+    a = lib.esp_decode_workspace_bytes(64, 860000, 131072, 32, 32, 128)
+    assert 0 < a < 64 << 20
+    assert lib.esp_decode_workspace_bytes(64, 860000, 131072, 32, 5, 128) == 0     # Hq % Hkv != 0
+
+
+def test_host_side_argument_errors(lib):
+    L = lib.lib
+    nul = ctypes.c_void_p(0)
+    one = ctypes.c_void_p(256)      # never dereferenced: every call below fails validation first
+    # merge: P out of range, bad D, null arrays
+    assert L.esp_merge_partials(one, one, 0, 4, 4, 128, one, nul, nul) == lib.ESP_ERR_INVALID_ARG
+    assert L.esp_merge_partials(one, one, 17, 4, 4, 128, one, nul, nul) == lib.ESP_ERR_INVALID_ARG
+    assert "P=17" in lib.last_error()
+    arr = (ctypes.c_void_p * 1)(256)
+    assert L.esp_merge_partials(arr, arr, 1, 4, 4, 64, one, nul, nul) == lib.ESP_ERR_UNSUPPORTED
+    assert L.esp_merge_partials(nul, arr, 1, 4, 4, 128, one, nul, nul) == lib.ESP_ERR_INVALID_ARG
+    # append
+    assert L.esp_kv_append(one, one, one, -1, one, one, 8, 4, 128, nul) == lib.ESP_ERR_INVALID_ARG
+    assert L.esp_kv_append(one, one, one, 4, one, one, 8, 4, 96, nul) == lib.ESP_ERR_UNSUPPORTED
+    assert L.esp_kv_append(nul, one, one, 4, one, one, 8, 4, 128, nul) == lib.ESP_ERR_INVALID_ARG
+    assert L.esp_kv_append(one, one, one, 0, one, one, 8, 4, 128, nul) == lib.ESP_OK     # nothing to do
+    # decode
+    f = ctypes.c_float(0.1)
+    assert L.esp_partial_attn_decode(one, one, one, 8, one, one, 2, 10, 5, 6, 4, 128, f, one, one, one, 1 << 20, nul) \
+        == lib.ESP_ERR_INVALID_ARG                                                         # Hq % Hkv
+    assert L.esp_partial_attn_decode(one, one, one, 8, one, one, 2, 10, 5, 4, 4, 64, f, one, one, one, 1 << 20, nul) \
+        == lib.ESP_ERR_UNSUPPORTED
+    assert L.esp_partial_attn_decode(one, one, one, 8, one, one, 2, 10, 5, 4, 4, 128, f, one, one, nul, 0, nul) \
+        == lib.ESP_ERR_WORKSPACE
+    assert L.esp_partial_attn_decode(one, one, one, 8, one, one, 2, 10, 5, 4, 4, 128, f, one, one, one, 16, nul) \
+        == lib.ESP_ERR_WORKSPACE
+    assert L.esp_partial_attn_decode(one, one, one, 8, one, one, 2, 10, 5, 12, 12, 128, f, one, one, one, 1 << 30, nul) \
+        == lib.ESP_ERR_UNSUPPORTED                                                         # Hkv = 12
+    assert L.esp_partial_attn_decode(one, one, one, 8, one, one, 0, 0, 0, 4, 4, 128, f, one, one, nul, 0, nul) == lib.ESP_OK
+    # prefill
+    args = dict(batch=1, Tq=16, Tkv=16, max_q=16, max_kv=16, Hq=4, Hkv=4, D=128)
+
+    def prefill(ws=one, ws_bytes=1 << 20, cu_q=nul, cu_kv=nul, **kw):
+        a = dict(args, **kw)
+        return L.esp_partial_attn_prefill(one, one, one, one, one, cu_q, cu_kv, a["batch"], a["Tq"], a["Tkv"], a["max_q"],
+                                          a["max_kv"], a["Hq"], a["Hkv"], a["D"], f, 1, one, one, ws, ws_bytes, nul)
+    assert prefill(D=64) == lib.ESP_ERR_UNSUPPORTED
+    assert prefill(Hq=6) == lib.ESP_ERR_INVALID_ARG
+    assert prefill(batch=2) == lib.ESP_ERR_INVALID_ARG              # batch > 1 without cu arrays
+    assert prefill(cu_q=one) == lib.ESP_ERR_INVALID_ARG             # only one of cu_q / cu_kv
+    assert prefill(ws=nul, ws_bytes=0) == lib.ESP_ERR_WORKSPACE
+    assert prefill(ws_bytes=8) == lib.ESP_ERR_WORKSPACE
+    assert prefill(ws=ctypes.c_void_p(8)) == lib.ESP_ERR_WORKSPACE  # misaligned
+    assert prefill(Tq=0, max_q=0) == lib.ESP_OK                     # nothing to do
+
+
+def test_no_oracle_or_fallback_in_product():
+    """The product path must not import the oracle (it is test infrastructure)."""
+    pkg = os.path.join(ROOT, "paper_2404_09526_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert "import oracle" not in text and "from oracle" not in text, fn
+                assert "esp_oracle" not in text, fn

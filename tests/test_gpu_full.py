@@ -1,0 +1,154 @@
+"""GPU parity at the benchmark's full sizes (configs 2-5), in the launch configuration bench.py times.
+The oracle cannot evaluate these in full, so it computes a seeded sample of outputs one by one:
+(request, head, row) triples for prefill (all heads, chunk and tile edges, rows with an empty visible set,
+random rows), whole requests for decode.  Per-shard partials and the merged result are both checked."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from esp_checks import check_o_lse, sample_rows
+from paper_2404_09526_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def esp(cuda):
+    from paper_2404_09526_amd import binding
+    return binding
+
+
+def say(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+def prefill_samples(pc, n_random_per_req, seed):
+    rng = np.random.default_rng(seed)
+    cu = wl.host_i32(pc.cu_q)
+    rows, reqs = [], []
+    for r in range(pc.batch):
+        rr = sample_rows(rng, int(cu[r]), int(cu[r + 1]), n_random_per_req)
+        rows.append(rr); reqs.append(np.full(len(rr), r))
+    rows, reqs = np.concatenate(rows), np.concatenate(reqs)
+    heads = (np.arange(len(rows)) * 7 + rng.integers(0, pc.Hq)) % pc.Hq      # cycles through every head
+    return rows.astype(np.int64), heads.astype(np.int64), reqs
+
+
+def check_prefill_sampled(esp, pc, n_random_per_req, seed):
+    rows, heads, reqs = prefill_samples(pc, n_random_per_req, seed)
+    assert set(heads.tolist()) == set(range(pc.Hq))
+    qb, qp = wl.bits(pc.q), wl.host_i32(pc.q_pos)
+    single = pc.batch == 1
+    parts, refs = [], []
+    for si, s in enumerate(pc.shards):
+        say(f"{pc.name} shard {si}: Tq={pc.Tq} Tkv={s.k.shape[0]} Hq={pc.Hq} Hkv={pc.Hkv} batch={pc.batch} samples={len(rows)}")
+        O, LSE = esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos,
+                                              None if single else pc.cu_q, None if single else s.cu_kv,
+                                              None if single else pc.max_q, None if single else s.max_kv,
+                                              softmax_scale=pc.scale, causal=pc.causal)
+        torch.cuda.synchronize()
+        cu_kv = wl.host_i32(s.cu_kv)
+        Or, Lr = oracle.partial_attn(qb, wl.bits(s.k), wl.bits(s.v), qp, wl.host_i32(s.kv_pos), pc.scale, pc.causal,
+                                     rows, heads, cu_kv[reqs], cu_kv[reqs + 1])
+        Og = O[torch.from_numpy(rows).to(O.device), torch.from_numpy(heads).to(O.device)].float().cpu().numpy()
+        Lg = LSE[torch.from_numpy(rows).to(O.device), torch.from_numpy(heads).to(O.device)].cpu().numpy()
+        st = check_o_lse(Og, Lg, Or, Lr, f"{pc.name} shard {si}")
+        say(f"  ok: {st}")
+        # properties that hold at any size: no NaN anywhere, LSE finite or -inf
+        assert not torch.isnan(O.float()).any() and not torch.isnan(LSE).any()
+        parts.append((O, LSE)); refs.append((Or, Lr))
+    if len(parts) > 1:
+        Om, Lm = esp.esp_merge_partials([p[0] for p in parts], [p[1] for p in parts])
+        torch.cuda.synchronize()
+        Oref, Lref = oracle.merge_partials(np.stack([r[0] for r in refs]), np.stack([r[1] for r in refs]))
+        ri, hi = torch.from_numpy(rows).to(Om.device), torch.from_numpy(heads).to(Om.device)
+        st = check_o_lse(Om[ri, hi].float().cpu().numpy(), Lm[ri, hi].cpu().numpy(), Oref, Lref, f"{pc.name} merged")
+        say(f"  merged ok: {st}")
+        # causal striped layout with r_q = 0: every row sees at least its own token in shard 0
+        assert torch.isfinite(Lm).all()
+
+
+def test_config2_prefill_striped_4_shards(esp, cuda):
+    pc = wl.config2_prefill(cuda)
+    assert pc.visible_pairs_per_head == 2 * 8192 * 8192 - 8192
+    check_prefill_sampled(esp, pc, 40, 102)
+    # stripe 0's first query sees nothing in shards 1..3 (kv positions 1, 2, 3 > 0)
+
+
+def test_config4_prefill_long_context(esp, cuda):
+    pc = wl.config4_prefill(cuda)
+    assert pc.visible_pairs_per_head == 32768 * 262144
+    check_prefill_sampled(esp, pc, 8, 104)
+
+
+def test_config5_prefill_varlen_gqa(esp, cuda):
+    pc = wl.config5_prefill(cuda)
+    assert pc.visible_pairs_per_head == 2994661376
+    check_prefill_sampled(esp, pc, 6, 105)
+
+
+def check_decode_sampled(esp, dc, sample, heads_per_req=None):
+    say(f"{dc.name}: B={dc.B} total={dc.total_tokens} max={int(dc.lens.max())} Hq={dc.Hq} Hkv={dc.Hkv} S={dc.num_slots} sample={sample}")
+    slots, off = wl.host_i32(dc.slot_idx), wl.host_i32(dc.seq_offsets)
+    assert len(np.unique(slots)) == len(slots)                      # unique, non-contiguous slots
+    kp = np.zeros((dc.num_slots, dc.Hkv, dc.D), np.uint16); vp = np.zeros_like(kp)   # lazily paged host image
+    for b in sample:
+        kr, vr = dc.host_rows[b]
+        oracle.kv_append(kr, vr, slots[off[b]:off[b + 1]], kp, vp)
+    O, LSE = esp.esp_partial_attn_decode(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, int(dc.lens.max()),
+                                         softmax_scale=dc.scale)
+    torch.cuda.synchronize()
+    hs_all = np.arange(dc.Hq, dtype=np.int64) if heads_per_req is None else heads_per_req
+    reqs = np.repeat(np.asarray(sample, np.int64), len(hs_all)); hs = np.tile(hs_all, len(sample))
+    Or, Lr = oracle.partial_attn_decode(wl.bits(dc.q), kp, vp, slots, off, dc.scale, reqs, hs)
+    st = check_o_lse(O.float().cpu().numpy()[reqs, hs], LSE.cpu().numpy()[reqs, hs], Or, Lr, dc.name)
+    say(f"  ok: {st}")
+    assert torch.isfinite(LSE).all() and not torch.isnan(O.float()).any()
+    # merge with the 3 synthetic peer partials (kernel test on the arrays the GPU merged)
+    Om, Lm = esp.esp_merge_partials([O] + list(dc.peer_O), [LSE] + list(dc.peer_LSE))
+    torch.cuda.synchronize()
+    Op = np.stack([oracle.bf16_bits_to_f64(wl.bits(t)) for t in [O] + list(dc.peer_O)])
+    Lp = np.stack([t.cpu().numpy().astype(np.float64) for t in [LSE] + list(dc.peer_LSE)])
+    Oref, Lref = oracle.merge_partials(Op, Lp)
+    check_o_lse(Om.float().cpu().numpy().reshape(-1, dc.D), Lm.cpu().numpy().reshape(-1), Oref.reshape(-1, dc.D),
+                Lref.reshape(-1), f"{dc.name} merge")
+    # append to random free slots: appended rows + 4096 random untouched rows on the host, whole-pool checksum on device
+    new_slots = wl.host_i32(dc.new_slots)
+    rng = np.random.default_rng(7)
+    probe = np.setdiff1d(rng.integers(0, dc.num_slots, 4096), new_slots)
+    pi = torch.from_numpy(probe).to(dc.k_pool.device)
+    before_k, before_v = wl.bits(dc.k_pool[pi]), wl.bits(dc.v_pool[pi])
+    sum_before = [int(p.view(torch.int16).sum(dtype=torch.int64).item()) for p in (dc.k_pool, dc.v_pool)]
+    esp.esp_kv_append(dc.new_k, dc.new_v, dc.new_slots, dc.k_pool, dc.v_pool)
+    torch.cuda.synchronize()
+    ni = torch.from_numpy(new_slots.astype(np.int64)).to(dc.k_pool.device)
+    assert np.array_equal(wl.bits(dc.k_pool[ni]), wl.bits(dc.new_k)) and np.array_equal(wl.bits(dc.v_pool[ni]), wl.bits(dc.new_v))
+    assert np.array_equal(wl.bits(dc.k_pool[pi]), before_k) and np.array_equal(wl.bits(dc.v_pool[pi]), before_v)
+    added = [int(t.view(torch.int16).sum(dtype=torch.int64).item()) for t in (dc.new_k, dc.new_v)]
+    sum_after = [int(p.view(torch.int16).sum(dtype=torch.int64).item()) for p in (dc.k_pool, dc.v_pool)]
+    assert sum_after[0] == sum_before[0] + added[0] and sum_after[1] == sum_before[1] + added[1]   # free slots were zero
+
+
+def pick_requests(lens, n):
+    order = np.argsort(lens)
+    picks = {int(order[0]), int(order[-1]), int(order[len(order) // 2])}
+    rng = np.random.default_rng(3)
+    while len(picks) < n:
+        picks.add(int(rng.integers(0, len(lens))))
+    return sorted(picks)
+
+
+def test_config3_decode_pool_4M_slots(esp, cuda):
+    lens = wl.lognormal_lengths(64, 8192, 1024, 131072, 2)
+    sample = pick_requests(lens, 10)
+    dc = wl.config3_decode(cuda, sample_reqs=sample)
+    assert dc.Hkv * dc.D * 2 * 2 == 16384                           # bytes per resident token (K and V rows)
+    check_decode_sampled(esp, dc, sample)
+
+
+def test_config5_decode_pool_16M_slots_gqa(esp, cuda):
+    lens = wl.lognormal_lengths(256, 16384, 512, 1 << 20, 4)
+    sample = pick_requests(lens, 10)
+    dc = wl.config5_decode(cuda, sample_reqs=sample)
+    check_decode_sampled(esp, dc, sample, heads_per_req=np.array([0, 5, 10, 15, 17, 22, 27, 28, 31], np.int64))

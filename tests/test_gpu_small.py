@@ -1,0 +1,242 @@
+"""GPU parity, small cases checked exhaustively against the CPU oracle (element by element):
+several tiles plus ragged tails, all striped offsets, var-len batches, GQA, unsorted positions,
+empty visible sets, empty requests, and config 1 of the benchmark in full."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from esp_checks import check_o_lse
+from paper_2404_09526_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def esp(cuda):
+    from paper_2404_09526_amd import binding
+    return binding
+
+
+def say(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+def run_prefill_case(esp, pc, check_merged=True):
+    """Runs every shard through the HIP path, checks each partial and the merged result."""
+    qb, qp = wl.bits(pc.q), wl.host_i32(pc.q_pos)
+    cu_q = wl.host_i32(pc.cu_q)
+    Tq, Hq, D = pc.q.shape
+    rows = np.repeat(np.arange(Tq, dtype=np.int64), Hq)
+    heads = np.tile(np.arange(Hq, dtype=np.int64), Tq)
+    req_of_row = np.searchsorted(cu_q, np.arange(Tq), side="right") - 1
+    single = pc.batch == 1
+    parts, refs = [], []
+    for si, s in enumerate(pc.shards):
+        say(f"{pc.name} shard {si}: Tq={Tq} Tkv={s.k.shape[0]} Hq={Hq} Hkv={pc.Hkv} batch={pc.batch} causal={pc.causal}")
+        O, LSE = esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos,
+                                              None if single else pc.cu_q, None if single else s.cu_kv,
+                                              None if single else pc.max_q, None if single else s.max_kv,
+                                              softmax_scale=pc.scale, causal=pc.causal)
+        torch.cuda.synchronize()
+        cu_kv = wl.host_i32(s.cu_kv)
+        lo, hi = cu_kv[req_of_row[rows]], cu_kv[req_of_row[rows] + 1]
+        Or, Lr = oracle.partial_attn(qb, wl.bits(s.k), wl.bits(s.v), qp, wl.host_i32(s.kv_pos), pc.scale, pc.causal,
+                                     rows, heads, lo, hi)
+        check_o_lse(O.float().cpu().numpy().reshape(-1, D), LSE.cpu().numpy().reshape(-1), Or, Lr,
+                    f"{pc.name} shard {si}")
+        parts.append((O, LSE)); refs.append((Or, Lr))
+    if check_merged and len(parts) > 1:
+        say(f"{pc.name} merge of {len(parts)} partials")
+        Om, Lm = esp.esp_merge_partials([p[0] for p in parts], [p[1] for p in parts])
+        torch.cuda.synchronize()
+        # pipeline check: the oracle merges ITS OWN fp64 partials = attention over the union of the shards
+        Oref, Lref = oracle.merge_partials(np.stack([r[0] for r in refs]), np.stack([r[1] for r in refs]))
+        check_o_lse(Om.float().cpu().numpy().reshape(-1, D), Lm.cpu().numpy().reshape(-1), Oref, Lref, f"{pc.name} merged")
+    return parts
+
+
+# ------------------------------------------------------------------ config 1, in full
+def test_config1_prefill_exhaustive(esp, cuda):
+    pc = wl.config1_prefill(cuda)
+    assert pc.visible_pairs_per_head == 131072 + 98432
+    run_prefill_case(esp, pc)
+
+
+def test_config1_merged_equals_unpartitioned_attention(esp, cuda):
+    """The GPU pipeline (2 partials -> merge) against the oracle run directly on the whole 1024-token KV."""
+    pc = wl.config1_prefill(cuda)
+    parts = [esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos, softmax_scale=pc.scale) for s in pc.shards]
+    Om, Lm = esp.esp_merge_partials([p[0] for p in parts], [p[1] for p in parts])
+    torch.cuda.synchronize()
+    k_all = np.concatenate([wl.bits(s.k) for s in pc.shards]); v_all = np.concatenate([wl.bits(s.v) for s in pc.shards])
+    pos = np.concatenate([wl.host_i32(s.kv_pos) for s in pc.shards])
+    Or, Lr = oracle.partial_attn_all(wl.bits(pc.q), k_all, v_all, wl.host_i32(pc.q_pos), pos, pc.scale, True)
+    check_o_lse(Om.float().cpu().numpy().reshape(-1, 128), Lm.cpu().numpy().reshape(-1), Or.reshape(-1, 128), Lr.reshape(-1),
+                "C1 pipeline")
+
+
+def run_decode_case(esp, dc, heads=None):
+    say(f"{dc.name}: B={dc.B} lens={dc.lens.tolist()[:8]}... total={dc.total_tokens} Hq={dc.Hq} Hkv={dc.Hkv} S={dc.num_slots}")
+    # oracle's own pool image, built by its own scatter from the host copies of the rows
+    kp = np.zeros((dc.num_slots, dc.Hkv, dc.D), np.uint16); vp = np.zeros_like(kp)
+    slots, off = wl.host_i32(dc.slot_idx), wl.host_i32(dc.seq_offsets)
+    for b, (kr, vr) in dc.host_rows.items():
+        oracle.kv_append(kr, vr, slots[off[b]:off[b + 1]], kp, vp)
+    O, LSE = esp.esp_partial_attn_decode(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets,
+                                         int(dc.lens.max()) if dc.B else 0, softmax_scale=dc.scale)
+    torch.cuda.synchronize()
+    reqs = np.repeat(np.array(sorted(dc.host_rows), np.int64), dc.Hq)
+    hs = np.tile(np.arange(dc.Hq, dtype=np.int64), len(dc.host_rows))
+    Or, Lr = oracle.partial_attn_decode(wl.bits(dc.q), kp, vp, slots, off, dc.scale, reqs, hs)
+    Og = O.float().cpu().numpy()[reqs, hs]; Lg = LSE.cpu().numpy()[reqs, hs]
+    check_o_lse(Og, Lg, Or, Lr, dc.name)
+    return O, LSE, kp, vp
+
+
+def test_config1_decode_append_merge(esp, cuda):
+    dc = wl.config1_decode(cuda)
+    O, LSE, kp, vp = run_decode_case(esp, dc)
+    # bit-exact pool before the append (the oracle image was built by the oracle's scatter)
+    assert np.array_equal(wl.bits(dc.k_pool), kp) and np.array_equal(wl.bits(dc.v_pool), vp)
+    # append 4 tokens to free slots: every slot of the pool is compared
+    oracle.kv_append(wl.bits(dc.new_k), wl.bits(dc.new_v), wl.host_i32(dc.new_slots), kp, vp)
+    esp.esp_kv_append(dc.new_k, dc.new_v, dc.new_slots, dc.k_pool, dc.v_pool)
+    torch.cuda.synchronize()
+    assert np.array_equal(wl.bits(dc.k_pool), kp) and np.array_equal(wl.bits(dc.v_pool), vp)
+    # merge with 3 synthetic peer partials: kernel test on the very arrays given to the GPU
+    Om, Lm = esp.esp_merge_partials([O] + list(dc.peer_O), [LSE] + list(dc.peer_LSE))
+    torch.cuda.synchronize()
+    Op = np.stack([oracle.bf16_bits_to_f64(wl.bits(t)) for t in [O] + list(dc.peer_O)])
+    Lp = np.stack([t.cpu().numpy().astype(np.float64) for t in [LSE] + list(dc.peer_LSE)])
+    Oref, Lref = oracle.merge_partials(Op, Lp)
+    check_o_lse(Om.float().cpu().numpy().reshape(-1, 128), Lm.cpu().numpy().reshape(-1), Oref.reshape(-1, 128),
+                Lref.reshape(-1), "C1 merge")
+
+
+# ------------------------------------------------------------------ prefill: layouts and edge cases
+@pytest.mark.parametrize("r_q", [0, 1, 2, 3])
+def test_striped_all_offsets(esp, cuda, r_q):
+    """Striped layout, every stripe as the local query: rows that see nothing in a shard (LSE = -inf) occur."""
+    pc = wl.striped_prefill(f"striped-rq{r_q}", [600], 4, r_q, 4, 4, 10 + r_q, cuda)
+    run_prefill_case(esp, pc)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (4, 1), (16, 8)])
+def test_gqa_varlen_batch_ragged(esp, cuda, Hq, Hkv):
+    """Var-len batch with lengths that are not multiples of the 64-row KV tile or the 256-row Q tile."""
+    pc = wl.striped_prefill(f"varlen-{Hq}/{Hkv}", [1, 63, 257, 300, 64], 2, 0, Hq, Hkv, 20, cuda)
+    run_prefill_case(esp, pc)
+
+
+def test_non_causal_and_tail(esp, cuda):
+    pc = wl.contiguous_prefill("noncausal", 130, 0, [(0, 200), (200, 333)], 4, 4, 21, cuda, causal=False)
+    run_prefill_case(esp, pc)
+
+
+def test_unsorted_positions(esp, cuda):
+    """Positions in arbitrary order (any token-level placement is legal): results must still be exact."""
+    pc = wl.contiguous_prefill("shuffled", 300, 500, [(0, 450), (450, 800)], 4, 2, 22, cuda)
+    g = torch.Generator(device="cpu").manual_seed(5)
+    for s in pc.shards:
+        perm = torch.randperm(s.kv_pos.numel(), generator=g).to(cuda)
+        s.kv_pos = s.kv_pos[perm].contiguous()           # rows keep their data, positions are shuffled
+    perm = torch.randperm(pc.q_pos.numel(), generator=g).to(cuda)
+    pc.q_pos = pc.q_pos[perm].contiguous()
+    run_prefill_case(esp, pc)
+
+
+def test_query_chunk_before_every_key(esp, cuda):
+    """A whole workgroup of queries sees nothing: O = 0, LSE = -inf everywhere, and the merge ignores it."""
+    pc = wl.contiguous_prefill("allhidden", 64, 0, [(1000, 1200), (0, 64)], 4, 4, 23, cuda)
+    parts = run_prefill_case(esp, pc)
+    assert torch.isneginf(parts[0][1]).all() and (parts[0][0] == 0).all()
+
+
+def test_prefill_is_deterministic(esp, cuda):
+    pc = wl.striped_prefill("det", [700], 4, 1, 4, 4, 24, cuda)
+    s = pc.shards[2]
+    a = esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos, softmax_scale=pc.scale)
+    b = esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos, softmax_scale=pc.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0].view(torch.int16), b[0].view(torch.int16)) and torch.equal(a[1].view(torch.int32), b[1].view(torch.int32))
+
+
+# ------------------------------------------------------------------ decode: edge cases
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (8, 4), (32, 8), (32, 32), (16, 16)])
+def test_decode_heads_and_empty_requests(esp, cuda, Hq, Hkv):
+    lens = [0, 1, 2, 3, 0, 65, 700, 5000, 0]
+    dc = wl.decode_pool(f"decode-{Hq}/{Hkv}", lens, 8192, Hq, Hkv, 30, cuda, n_new=7, skip_new_every=3)
+    O, LSE, kp, vp = run_decode_case(esp, dc)
+    assert torch.isneginf(LSE[[0, 4, 8]]).all() and (O[[0, 4, 8]] == 0).all()
+    oracle.kv_append(wl.bits(dc.new_k), wl.bits(dc.new_v), wl.host_i32(dc.new_slots), kp, vp)
+    esp.esp_kv_append(dc.new_k, dc.new_v, dc.new_slots, dc.k_pool, dc.v_pool)
+    torch.cuda.synchronize()
+    assert np.array_equal(wl.bits(dc.k_pool), kp) and np.array_equal(wl.bits(dc.v_pool), vp)
+
+
+def test_decode_many_ranges(esp, cuda):
+    """Enough tokens that the token list is cut into many ranges, with requests spanning several of them."""
+    lens = wl.lognormal_lengths(24, 3000, 10, 40000, 31)
+    dc = wl.decode_pool("decode-ranges", lens, 1 << 18, 8, 8, 31, cuda, n_new=0)
+    run_decode_case(esp, dc)
+
+
+def test_decode_is_deterministic(esp, cuda):
+    dc = wl.decode_pool("decode-det", [900, 33, 4000], 8192, 8, 4, 32, cuda, n_new=0)
+    a = esp.esp_partial_attn_decode(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, 4000)
+    b = esp.esp_partial_attn_decode(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, 4000)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0].view(torch.int16), b[0].view(torch.int16)) and torch.equal(a[1].view(torch.int32), b[1].view(torch.int32))
+
+
+# ------------------------------------------------------------------ merge kernel on its own
+@pytest.mark.parametrize("P", [1, 2, 4, 16])
+def test_merge_kernel(esp, cuda, P):
+    g = torch.Generator(device=cuda).manual_seed(40 + P)
+    T, H = 37, 8
+    Os = [wl.randn_bf16((T, H, 128), g, cuda) for _ in range(P)]
+    Ls = [torch.randn((T, H), generator=g, device=cuda) * 4 for _ in range(P)]
+    if P > 1:
+        Ls[1][::3] = float("-inf")                       # an empty partial here and there
+        for L in Ls:
+            L[5] = float("-inf")                         # a row that is empty in every partial
+        Os[1][::3] = float("nan")                        # garbage in an empty partial must not leak
+    say(f"merge P={P}")
+    Om, Lm = esp.esp_merge_partials(Os, Ls)
+    torch.cuda.synchronize()
+    Op = np.stack([oracle.bf16_bits_to_f64(wl.bits(o)) for o in Os]); Lp = np.stack([l.cpu().numpy().astype(np.float64) for l in Ls])
+    Op = np.nan_to_num(Op, nan=0.0)
+    Oref, Lref = oracle.merge_partials(Op, Lp)
+    check_o_lse(Om.float().cpu().numpy().reshape(-1, 128), Lm.cpu().numpy().reshape(-1), Oref.reshape(-1, 128), Lref.reshape(-1),
+                f"merge P={P}")
+    # in place (O aliases the first partial) and without LSE output
+    O0 = Os[0].clone()
+    esp.esp_merge_partials([O0] + Os[1:], Ls, O=O0, want_lse=False)
+    torch.cuda.synchronize()
+    assert torch.equal(O0.view(torch.int16), Om.view(torch.int16))
+
+
+def test_device_side_errors_are_reported_not_thrown(esp, cuda):
+    q = torch.zeros((4, 4, 64), dtype=torch.bfloat16, device=cuda)
+    with pytest.raises(esp.EspError) as e:
+        esp.esp_merge_partials([q], [torch.zeros((4, 4), device=cuda)])
+    assert e.value.status == esp.ESP_ERR_UNSUPPORTED
+
+
+def test_request_without_keys_in_this_shard(esp, cuda):
+    """Multi-request batch where the first request holds no row of the shard (cu_kv repeats an offset)."""
+    pc = wl.striped_prefill("nokeys", [100, 80], 2, 0, 4, 4, 25, cuda)
+    s = pc.shards[1]
+    k, v, kv_pos = s.k[100:].contiguous(), s.v[100:].contiguous(), s.kv_pos[100:].contiguous()
+    cu_kv = torch.tensor([0, 0, 80], dtype=torch.int32, device=cuda)
+    say("nokeys: request 0 has queries but no keys")
+    O, LSE = esp.esp_partial_attn_prefill(pc.q, k, v, pc.q_pos, kv_pos, pc.cu_q, cu_kv, 100, 80, softmax_scale=pc.scale)
+    torch.cuda.synchronize()
+    assert torch.isneginf(LSE[:100]).all() and (O[:100] == 0).all()
+    rows = np.repeat(np.arange(100, 180, dtype=np.int64), 4); heads = np.tile(np.arange(4, dtype=np.int64), 80)
+    Or, Lr = oracle.partial_attn(wl.bits(pc.q), wl.bits(k), wl.bits(v), wl.host_i32(pc.q_pos), wl.host_i32(kv_pos), pc.scale,
+                                 True, rows, heads)
+    check_o_lse(O[100:].float().cpu().numpy().reshape(-1, 128), LSE[100:].cpu().numpy().reshape(-1), Or, Lr, "nokeys")
