@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the ESP attention hot path on ONE MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input, already resident in HBM:
+    prefill partial attention of the local query chunk against each of the 4 striped KV shards
+    -> merge of the 4 partials -> KV append of the new decode tokens into free pool slots
+    -> decode partial attention over the token pool -> merge with 3 peer partials.
+Default workload: the LWM-7B (Llama-2-7B shape, 32 heads x 128, MHA) shares of the benchmark spec:
+configs[1] for prefill (8192-token chunk, 4 x 8192 striped KV) and configs[2] for decode (64 requests,
+lognormal KV slices in a 4M-slot pool).  `value` is the prefill TFLOP/s; the decode GB/s is reported in
+the same line (`decode`), each with its roofline object.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="lwm7b", choices=["lwm7b", "long", "mixed"],
+                    help="lwm7b = configs[1]+configs[2] (default, the bench line); long = configs[3]; mixed = configs[4]")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-json", default=None, help="JSON file with measured HBM bytes per launch (from rocprofv3 --pmc)")
+    return ap.parse_args()
+
+
+def cpu_baseline(pc, dc, wl, oracle):
+    """The oracle as it stands, timed on this host's cores on a bounded sample of the same workload."""
+    import numpy as np
+    out = {"kind": "oracle", "cores": oracle.num_threads()}
+    sample = []
+    if pc is not None:
+        rng = np.random.default_rng(0)
+        n = 98304                               # about 10 s of fp64 work on 16 cores
+        rows = rng.integers(0, pc.Tq, n).astype(np.int64)
+        heads = rng.integers(0, pc.Hq, n).astype(np.int64)
+        cu_q = wl.host_i32(pc.cu_q)
+        reqs = np.searchsorted(cu_q, rows, side="right") - 1
+        s = pc.shards[0]
+        cu_kv = wl.host_i32(s.cu_kv)
+        qb, kb, vb = wl.bits(pc.q), wl.bits(s.k), wl.bits(s.v)
+        qp, kp = wl.host_i32(pc.q_pos), wl.host_i32(s.kv_pos)
+        lo, hi = cu_kv[reqs], cu_kv[reqs + 1]
+        # visible pairs of the sample, to convert seconds into the metric's unit
+        pairs = 0
+        for r in range(pc.batch):
+            m = reqs == r
+            if m.any():
+                seg = np.sort(kp[cu_kv[r]:cu_kv[r + 1]])
+                pairs += int(np.searchsorted(seg, qp[rows[m]], side="right").sum()) if pc.causal else int(m.sum()) * len(seg)
+        t0 = time.perf_counter()
+        oracle.partial_attn(qb, kb, vb, qp, kp, pc.scale, pc.causal, rows, heads, lo, hi)
+        dt = time.perf_counter() - t0
+        out["value"] = 4.0 * pc.D * pairs / dt / 1e12
+        out["unit"] = "TFLOP/s"
+        out["seconds"] = dt
+        sample.append(f"prefill: {n} random (row, head) pairs of shard 0 against the full shard ({pairs} visible pairs)")
+        out["extrapolated_full_prefill_s"] = dt * pc.visible_pairs_per_head * pc.Hq / max(pairs, 1)
+    if dc is not None:
+        import numpy as np
+        slots, off = wl.host_i32(dc.slot_idx), wl.host_i32(dc.seq_offsets)
+        kpool = np.zeros((dc.num_slots, dc.Hkv, dc.D), np.uint16)
+        vpool = np.zeros_like(kpool)
+        reqs_s = sorted(dc.host_rows)
+        tok = 0
+        for b in reqs_s:
+            kr, vr = dc.host_rows[b]
+            oracle.kv_append(kr, vr, slots[off[b]:off[b + 1]], kpool, vpool)
+            tok += int(off[b + 1] - off[b])
+        heads = np.arange(dc.Hq, dtype=np.int64)
+        reqs = np.repeat(np.asarray(reqs_s, np.int64), len(heads))
+        hs = np.tile(heads, len(reqs_s))
+        t0 = time.perf_counter()
+        oracle.partial_attn_decode(wl.bits(dc.q), kpool, vpool, slots, off, dc.scale, reqs, hs)
+        dt = time.perf_counter() - t0
+        # bytes the oracle touched: K and V rows of the sampled heads only
+        byts = tok * len(heads) * 2 * dc.D * 2
+        out["decode_value"] = byts / dt / 1e9
+        out["decode_unit"] = "GB/s"
+        out["decode_seconds"] = dt
+        sample.append(f"decode: requests {reqs_s} x {len(heads)} heads ({tok} resident tokens)")
+    out["sample"] = "; ".join(sample)
+    return out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1. "
+              "DESIGN.md describes how the path would shard.", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2404_09526_amd import binding as esp, workloads as wl
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    pc = dc = None
+    if args.workload == "lwm7b":
+        pc = wl.config2_prefill(dev)
+        lens = wl.lognormal_lengths(64, 8192, 1024, 131072, 2)
+        order = np.argsort(lens)
+        dc = wl.config3_decode(dev, sample_reqs=[int(i) for i in order[::4]])
+        name = "LWM-7B shape: prefill chunk 8192 x 4 striped shards of 8192 (configs[1]) + decode B=64 in a 4M-slot pool (configs[2])"
+    elif args.workload == "long":
+        pc = wl.config4_prefill(dev)
+        name = "long-context prefill share: chunk 32768 against 262144 local KV (configs[3])"
+    else:
+        pc = wl.config5_prefill(dev)
+        lens = wl.lognormal_lengths(256, 16384, 512, 1 << 20, 4)
+        order = np.argsort(lens)
+        dc = wl.config5_decode(dev, sample_reqs=[int(order[0]), int(order[len(order) // 2])])
+        name = "mixed iteration: var-len GQA prefill of 6 requests x 4 striped shards + decode B=256 in a 16M-slot pool (configs[4])"
+
+    single = pc.batch == 1
+    ws_pf = torch.empty(max(esp.esp_prefill_workspace_bytes(pc.Tq, pc.shards[0].k.shape[0], pc.batch, pc.Hq, pc.Hkv, pc.D), 256),
+                        dtype=torch.uint8, device=dev)
+    part_O = [torch.empty_like(pc.q) for _ in pc.shards]
+    part_L = [torch.empty((pc.Tq, pc.Hq), dtype=torch.float32, device=dev) for _ in pc.shards]
+    out_O = torch.empty_like(pc.q)
+    out_L = torch.empty((pc.Tq, pc.Hq), dtype=torch.float32, device=dev)
+    if dc is not None:
+        max_len = int(dc.lens.max())
+        ws_dc = torch.empty(esp.esp_decode_workspace_bytes(dc.B, dc.total_tokens, max_len, dc.Hq, dc.Hkv, dc.D),
+                            dtype=torch.uint8, device=dev)
+        dO = torch.empty_like(dc.q)
+        dL = torch.empty((dc.B, dc.Hq), dtype=torch.float32, device=dev)
+        mO = torch.empty_like(dc.q)
+        mL = torch.empty_like(dL)
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def step(rec=None):
+        e = [ev() for _ in range(6)] if rec is not None else None
+        if e: e[0].record()
+        for i, s in enumerate(pc.shards):
+            esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos,
+                                         None if single else pc.cu_q, None if single else s.cu_kv,
+                                         None if single else pc.max_q, None if single else s.max_kv,
+                                         softmax_scale=pc.scale, causal=pc.causal, O=part_O[i], LSE=part_L[i], workspace=ws_pf)
+        if e: e[1].record()
+        if len(pc.shards) > 1:
+            esp.esp_merge_partials(part_O, part_L, O=out_O, LSE=out_L)
+        if e: e[2].record()
+        if dc is not None:
+            esp.esp_kv_append(dc.new_k, dc.new_v, dc.new_slots, dc.k_pool, dc.v_pool)
+            if e: e[3].record()
+            esp.esp_partial_attn_decode(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, max_len,
+                                        softmax_scale=dc.scale, O=dO, LSE=dL, workspace=ws_dc)
+            if e: e[4].record()
+            esp.esp_merge_partials([dO] + list(dc.peer_O), [dL] + list(dc.peer_LSE), O=mO, LSE=mL)
+            if e: e[5].record()
+        if rec is not None:
+            rec.append(e)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    recs = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(recs)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    def avg(i, j):
+        return sum(e[i].elapsed_time(e[j]) for e in recs) / len(recs)   # ms
+
+    ms_prefill = avg(0, 1)
+    ms_merge = avg(1, 2) if len(pc.shards) > 1 else 0.0
+    flops = pc.flops()
+    tflops = flops / (ms_prefill * 1e-3) / 1e12
+    n_calls = len(pc.shards)
+    result = {
+        "metric": "prefill partial-attn TFLOP/s + decode partial-attn HBM GB/s (% of peak)",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": name, "Hq": pc.Hq, "Hkv": pc.Hkv, "head_dim": pc.D, "prefill_Tq": pc.Tq,
+                   "prefill_shards": n_calls, "prefill_flops": flops},
+        "prefill": {"ms_all_shards": ms_prefill, "ms_per_shard_call": ms_prefill / n_calls, "ms_merge": ms_merge,
+                    "tflops": tflops, "pct_of_peak": 100.0 * tflops / PEAK_BF16_TFLOPS},
+        "roofline": {"kernel": "prefill_kernel", "bound": "mfma", "achieved": tflops, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "launch_ms": ms_prefill / n_calls, "flops_per_launch": flops / n_calls},
+    }
+    if dc is not None:
+        ms_append, ms_decode, ms_dmerge = avg(2, 3), avg(3, 4), avg(4, 5)
+        byts = dc.kv_bytes()
+        gbs = byts / (ms_decode * 1e-3) / 1e9
+        result["decode"] = {"ms": ms_decode, "ms_append": ms_append, "ms_merge": ms_dmerge, "bytes": byts, "gbs": gbs,
+                            "pct_of_peak": 100.0 * gbs / PEAK_HBM_GBS, "B": dc.B, "total_tokens": dc.total_tokens,
+                            "sigma": 1.0}
+        result["roofline_decode"] = {"kernel": "decode_partial_kernel", "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS,
+                                     "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "traffic": None, "launch_ms": ms_decode,
+                                     "bytes_per_launch": byts}
+        result["config"].update({"decode_B": dc.B, "decode_total_tokens": dc.total_tokens, "pool_slots": dc.num_slots})
+    if args.traffic_json and os.path.exists(args.traffic_json):
+        tr = json.load(open(args.traffic_json))
+        result["roofline"]["traffic"] = tr.get("prefill_kernel")
+        if "roofline_decode" in result:
+            result["roofline_decode"]["traffic"] = tr.get("decode_partial_kernel")
+    if not args.no_cpu_baseline:
+        import oracle
+        result["cpu_baseline"] = cpu_baseline(pc, dc, wl, oracle)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
