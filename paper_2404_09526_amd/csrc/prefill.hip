@@ -87,15 +87,28 @@ __device__ __forceinline__ float half_swap_sum(float x) {
     return lo + hi;
 }
 
+// LDS barrier that does not wait for outstanding global loads (the prefetch of a later tile stays
+// in flight across it): LDS traffic of this wavefront is drained, then the workgroup meets.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+constexpr int kStages = 3;          // LDS stages per operand; tile j of the visible sequence lives in stage j % 3
+constexpr float kRescaleStep = 8.f; // the running max is refreshed only when it grows by more than 2^8
+
+// Schedule inside a workgroup: the two wavefronts that share a SIMD (w and w + 4) run half an iteration
+// apart.  While one is in its matrix phase (O^T += V^T P^T of tile i, then S^T = K Q^T of tile i + 1) the
+// other is in its vector phase (mask, running max, exp2, row sum, bf16 pack of its tile), so the MFMA pipe
+// and the vector ALU of the SIMD are busy at the same time.  Phases are separated by workgroup barriers;
+// group B (wavefronts 4-7) passes one extra barrier before its loop and group A one after it.
 __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
-    __shared__ __attribute__((aligned(16))) unsigned char lds_k[2][kTileBytes];
-    __shared__ __attribute__((aligned(16))) unsigned char lds_v[2][kTileBytes];
-    __shared__ __attribute__((aligned(16))) int32_t lds_pos[2][kBN];
+    __shared__ __attribute__((aligned(16))) unsigned char lds_k[kStages][kTileBytes];
+    __shared__ __attribute__((aligned(16))) unsigned char lds_v[kStages][kTileBytes];
+    __shared__ __attribute__((aligned(16))) int32_t lds_pos[kStages][kBN];
     __shared__ int32_t lds_qmm[2][kPfWaves];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool group_b = wave >= kPfWaves / 2;
     const int G = a.Hq / a.Hkv;
 
     // ---- which (query tile, head): XCD-aware (consecutive workgroup ids land on consecutive
@@ -140,6 +153,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         tile0 = first_kv_tile;
     }
     const int nkt = (kv_hi - kv_lo + kBN - 1) / kBN;
+    const bool ragged_tail = (kv_hi - kv_lo) % kBN != 0;
 
     // ---- this lane's query row (column of S^T) and its Q fragment
     const int qi = lane & 31, hi = lane >> 5;
@@ -181,9 +195,8 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
 
     // ---- operand read offsets
     // K (A operand of S^T): row 32*kvb + qi, chunk 2t + hi
-    uint32_t k_rd[8];
-#pragma unroll
-    for (int t = 0; t < 8; ++t) k_rd[t] = qi * 256 + (((2 * t + hi) ^ (qi & 15)) << 4);
+    const uint32_t k_row = qi * 256, k_x = qi & 15;
+    auto k_rd = [&](int t) { return k_row + (((2 * t + hi) ^ k_x) << 4); };
     // V (A operand of O^T) by transposing reads: 16 lanes fetch a 4 (kv) x 16 (d) patch
     const int j = lane & 15, jq = j >> 2, dblk = (lane >> 4) & 1;
     uint32_t v_rd[4];
@@ -196,15 +209,9 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     for (int db = 0; db < 4; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
-    float m2 = -INFINITY;   // running max of scale*log2(e)*score
-    float lsum = 0.f;       // running sum of exp2 over this lane's half of the keys
+    float m_ref = -INFINITY;   // exponent offset in use (scale*log2(e)*score units); trails the true max by <= 2^8
+    float lsum = 0.f;          // running sum of exp2 over this lane's half of the keys
 
-    // ---- tile schedule: skip tiles no row of the workgroup can see
-    auto next_tile = [&](int t) {
-        if (a.causal)
-            while (t < nkt && a.tile_mm[tile0 + t].x > wg_qmax) ++t;
-        return t;
-    };
     uint4 gk0, gk1, gv0, gv1;
     int gpos = INT_MAX;
     auto load_tile = [&](int t) {
@@ -219,101 +226,188 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
             gpos = r < kv_hi ? a.kv_pos[r] : INT_MAX;
         }
     };
-    auto store_tile = [&](int buf) {
-        *(uint4*)(lds_k[buf] + st_k0) = gk0;
-        *(uint4*)(lds_k[buf] + st_k1) = gk1;
-        *(uint4*)(lds_v[buf] + st_v0) = gv0;
-        *(uint4*)(lds_v[buf] + st_v1) = gv1;
-        if (tid < kBN) lds_pos[buf][tid] = gpos;
+    auto store_tile = [&](int st) {
+        *(uint4*)(lds_k[st] + st_k0) = gk0;
+        *(uint4*)(lds_k[st] + st_k1) = gk1;
+        *(uint4*)(lds_v[st] + st_v0) = gv0;
+        *(uint4*)(lds_v[st] + st_v1) = gv1;
+        if (tid < kBN) lds_pos[st][tid] = gpos;
     };
 
-    int kt = next_tile(0);
-    int buf = 0;
-    if (kt < nkt) { load_tile(kt); store_tile(0); }
-    __syncthreads();
+    floatx16 sacc[2];          // S^T of the tile in flight, then its probabilities
+    union PFrag { uint32_t u[4]; bf16x8 v; };
+    PFrag pf[2][2];            // P^T packed to bf16: [kvb][t2]
+    // per-tile facts, wavefront-uniform, from the tile's (min, max) position
+    auto tile_needs_mask = [&](int t, int2 mm) {
+        return (ragged_tail && t == nkt - 1) || (a.causal && mm.y > wave_qmin);
+    };
 
-    while (kt < nkt) {
-        const int kt_next = next_tile(kt + 1);
-        if (kt_next < nkt) load_tile(kt_next);
-
-        const int2 mm = a.tile_mm[tile0 + kt];
-        const bool tail = (kt == nkt - 1) && ((kv_hi - kv_lo) % kBN != 0);
-        const bool wave_sees = mm.x <= wave_qmax;                 // else: hidden from all 32 rows
-        const bool need_mask = tail || mm.y > wave_qmin;
-        if (wave_sees) {
-            // ---- S^T = K Q^T : two 32x32 blocks along KV
-            floatx16 sacc[2];
+    // Operand fragments are fetched from LDS in batches of four MFMAs, two batches ahead of their use,
+    // so that the LDS latency hides behind the MFMAs of earlier batches.  Batches 0-3: V^T fragments of
+    // O^T += V^T P^T (two transposing reads each); batches 4-7: K fragments of S^T = K Q^T.
+    union VFrag { short4_t s[2]; bf16x8 v; };
+    VFrag fr[2][4];
+    auto read_batch = [&](int bi, int slot, int st_v, int st_k) {
+        if (bi < 4) {
+            const int kvb = bi >> 1, t2 = bi & 1;
 #pragma unroll
-            for (int kvb = 0; kvb < 2; ++kvb) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) sacc[kvb][r] = 0.f;
-#pragma unroll
-                for (int t = 0; t < 8; ++t) {
-                    bf16x8 kf = *(const bf16x8*)(lds_k[buf] + kvb * 8192 + k_rd[t]);
-                    sacc[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t], sacc[kvb], 0, 0, 0);
-                }
+            for (int db = 0; db < 4; ++db) {
+                const unsigned char* vp = lds_v[st_v] + (32 * kvb + 16 * t2) * 256 + v_rd[db];
+                fr[slot][db].s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ESP_LDS short4_t*)(vp));
+                fr[slot][db].s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ESP_LDS short4_t*)(vp + 8 * 256));
             }
-            if (need_mask) {
+        } else {
+            const int tp = bi - 4;   // t = 2*tp, 2*tp + 1
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const int t = 2 * tp + (x >> 1), kvb = x & 1;
+                fr[slot][x].v = *(const bf16x8*)(lds_k[st_k] + kvb * 8192 + k_rd(t));
+            }
+        }
+    };
+    auto mfma_batch = [&](int bi, int slot) {
+        if (bi < 4) {
+            const int kvb = bi >> 1, t2 = bi & 1;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[slot][db].v, pf[kvb][t2].v, oacc[db], 0, 0, 0);
+        } else {
+            const int tp = bi - 4;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const int t = 2 * tp + (x >> 1), kvb = x & 1;
+                sacc[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[slot][x].v, qf[t], sacc[kvb], 0, 0, 0);
+            }
+        }
+    };
+    // runs batches [first, last); the fragments of the first `primed` batches are already in flight
+    auto matrix_phase = [&](int first, int last, int primed, int st_v, int st_k) {
+#pragma unroll
+        for (int bi = first; bi < last; ++bi) {
+            if (bi == first) {
+#pragma unroll
+                for (int pb = first + primed; pb < first + 2 && pb < last; ++pb) read_batch(pb, pb % 2, st_v, st_k);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (bi == 4)
 #pragma unroll
                 for (int kvb = 0; kvb < 2; ++kvb)
 #pragma unroll
-                    for (int bb = 0; bb < 4; ++bb) {
-                        int4 kp = *(const int4*)(&lds_pos[buf][32 * kvb + 8 * bb + 4 * hi]);
-                        if (kp.x > my_qpos) sacc[kvb][4 * bb + 0] = -INFINITY;
-                        if (kp.y > my_qpos) sacc[kvb][4 * bb + 1] = -INFINITY;
-                        if (kp.z > my_qpos) sacc[kvb][4 * bb + 2] = -INFINITY;
-                        if (kp.w > my_qpos) sacc[kvb][4 * bb + 3] = -INFINITY;
-                    }
-            }
-            // ---- online softmax in the exp2 domain
-            float tmax = sacc[0][0];
-#pragma unroll
-            for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, sacc[0][r]);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sacc[1][r]);
-            tmax = half_swap_max(tmax);
-            const float m_new = fmaxf(m2, tmax * a.scale_log2);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;   // all keys hidden so far
-            const float alpha = __builtin_amdgcn_exp2f(m2 - m_use);
-            m2 = m_new;
-            float psum = 0.f;
+                    for (int r = 0; r < 16; ++r) sacc[kvb][r] = 0.f;
+            mfma_batch(bi, bi % 2);
+            if (bi + 2 < last) read_batch(bi + 2, bi % 2, st_v, st_k);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    auto softmax = [&](int st, bool need_mask) {
+        if (need_mask) {
 #pragma unroll
             for (int kvb = 0; kvb < 2; ++kvb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float p = __builtin_amdgcn_exp2f(fmaf(sacc[kvb][r], a.scale_log2, -m_use));
-                    sacc[kvb][r] = p;
-                    psum += p;
+                for (int bb = 0; bb < 4; ++bb) {
+                    int4 kp = *(const int4*)(&lds_pos[st][32 * kvb + 8 * bb + 4 * hi]);
+                    if (kp.x > my_qpos) sacc[kvb][4 * bb + 0] = -INFINITY;
+                    if (kp.y > my_qpos) sacc[kvb][4 * bb + 1] = -INFINITY;
+                    if (kp.z > my_qpos) sacc[kvb][4 * bb + 2] = -INFINITY;
+                    if (kp.w > my_qpos) sacc[kvb][4 * bb + 3] = -INFINITY;
                 }
-            lsum = lsum * alpha + psum;
+        }
+        float tmax = sacc[0][0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, sacc[0][r]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sacc[1][r]);
+        tmax = half_swap_max(tmax) * a.scale_log2;
+        // refresh the exponent offset only when the row max outgrew it by more than 2^8 (or at the first
+        // visible key): probabilities stay <= 2^8, which bf16 and the fp32 sums hold without loss
+        const bool grow = tmax > m_ref + kRescaleStep;   // false while everything is still hidden (-inf > -inf)
+        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+            const float m_new = grow ? tmax : m_ref;
+            const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_ref - m_new);
+            m_ref = m_new;
+            lsum *= alpha;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-            // ---- O^T += V^T P^T
-#pragma unroll
-            for (int kvb = 0; kvb < 2; ++kvb)
-#pragma unroll
-                for (int t2 = 0; t2 < 2; ++t2) {
-                    union { uint32_t u[4]; bf16x8 v; } pf;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        pf.u[e] = pack_bf16(sacc[kvb][8 * t2 + 2 * e], sacc[kvb][8 * t2 + 2 * e + 1]);
-#pragma unroll
-                    for (int db = 0; db < 4; ++db) {
-                        const unsigned char* vp = lds_v[buf] + (32 * kvb + 16 * t2) * 256 + v_rd[db];
-                        union { short4_t s[2]; bf16x8 v; } vf;
-                        vf.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ESP_LDS short4_t*)(vp));
-                        vf.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ESP_LDS short4_t*)(vp + 8 * 256));
-                        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf.v, oacc[db], 0, 0, 0);
-                    }
-                }
         }
-        if (kt_next < nkt) store_tile(buf ^ 1);
-        __syncthreads();
-        buf ^= 1;
-        kt = kt_next;
+        const float m_use = (m_ref == -INFINITY) ? 0.f : m_ref;   // all keys hidden so far: exp2(-inf - 0) = 0
+        float psum = 0.f;
+#pragma unroll
+        for (int kvb = 0; kvb < 2; ++kvb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float p = __builtin_amdgcn_exp2f(fmaf(sacc[kvb][r], a.scale_log2, -m_use));
+                sacc[kvb][r] = p;
+                psum += p;
+            }
+        lsum += psum;
+#pragma unroll
+        for (int kvb = 0; kvb < 2; ++kvb)
+#pragma unroll
+            for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    pf[kvb][t2].u[e] = pack_bf16(sacc[kvb][8 * t2 + 2 * e], sacc[kvb][8 * t2 + 2 * e + 1]);
+    };
+
+    // ---- sequence of visible tiles (skipping tiles no row of the workgroup can see), with their (min, max)
+    auto tile_mm_at = [&](int t) {
+        const int2* p = a.tile_mm + __builtin_amdgcn_readfirstlane(tile0 + t);   // uniform: a scalar load
+        return *p;
+    };
+    auto next_tile = [&](int t, int2& mm) {
+        mm = make_int2(0, 0);
+        if (a.causal) {
+            while (t < nkt) {
+                mm = tile_mm_at(t);
+                if (mm.x <= wg_qmax) break;
+                ++t;
+            }
+        }
+        return t;
+    };
+
+    // ---- prologue: tiles 0 and 1 of the visible sequence into LDS, tile 2 into registers, S of tile 0
+    // (a wavefront whose 32 rows cannot see a tile still runs it, fully masked: it would only wait at the
+    //  barriers otherwise, and one straight-line loop body keeps the register allocation tight)
+    int2 mm_cur, mm_nxt, mm_wr, mm_ld = make_int2(0, 0);
+    int t_cur = next_tile(0, mm_cur);                                   // tile whose S is in sacc / P in pf
+    int t_nxt = t_cur < nkt ? next_tile(t_cur + 1, mm_nxt) : nkt;       // tile of the next S
+    int t_wr = t_nxt < nkt ? next_tile(t_nxt + 1, mm_wr) : nkt;         // tile in registers, next to enter LDS
+    if (t_cur < nkt) { load_tile(t_cur); store_tile(0); }
+    if (t_nxt < nkt) { load_tile(t_nxt); store_tile(1); }
+    if (t_wr < nkt) load_tile(t_wr);
+    lds_barrier();
+    if (t_cur < nkt) matrix_phase(4, 8, 0, 0, 0);
+    if (group_b) lds_barrier();
+
+    int st_cur = 0;                                // LDS stage of t_cur
+    while (t_cur < nkt) {
+        // ---- vector phase: softmax of tile t_cur; bookkeeping of the tile to prefetch
+        const int st_nxt = st_cur == kStages - 1 ? 0 : st_cur + 1;
+        const int st_wr = st_nxt == kStages - 1 ? 0 : st_nxt + 1;
+        int t_ld = nkt;
+        if (t_wr < nkt) t_ld = next_tile(t_wr + 1, mm_ld);
+        softmax(st_cur, tile_needs_mask(t_cur, mm_cur));
+        // first fragments of the matrix phase: their tile has been in LDS for a whole iteration
+#pragma unroll
+        for (int pb = 0; pb < 2; ++pb) read_batch(pb, pb, st_cur, st_nxt);
+        asm volatile("s_barrier" ::: "memory");    // nothing of this wavefront's LDS traffic is awaited by others
+        // ---- matrix phase: stage tile t_wr, prefetch the one after it, PV of t_cur, S of t_nxt
+        // (after the last tile the S product runs on a stale stage and is discarded)
+        if (t_wr < nkt) {
+            store_tile(st_wr);
+            if (t_ld < nkt) load_tile(t_ld);
+        }
+        matrix_phase(0, 8, 2, st_cur, st_nxt);
+        lds_barrier();
+        t_cur = t_nxt; t_nxt = t_wr; t_wr = t_ld;
+        mm_cur = mm_nxt; mm_nxt = mm_wr; mm_wr = mm_ld;
+        st_cur = st_nxt;
     }
+    if (!group_b) lds_barrier();
 
     // ---- epilogue: normalise, write O (bf16) and LSE (natural log)
     const float ltot = half_swap_sum(lsum);
@@ -330,7 +424,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
                 *(uint2*)(op + 32 * db + 8 * bb) = w;
             }
         if (hi == 0)
-            a.LSE[(int64_t)my_row * a.Hq + h] = ltot > 0.f ? (m2 + __builtin_amdgcn_logf(ltot)) * kLn2 : -INFINITY;
+            a.LSE[(int64_t)my_row * a.Hq + h] = ltot > 0.f ? (m_ref + __builtin_amdgcn_logf(ltot)) * kLn2 : -INFINITY;
     }
 }
 
