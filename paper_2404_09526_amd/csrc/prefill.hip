@@ -189,9 +189,13 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     const uint32_t st_k1 = st_row1 * 256 + ((st_ch ^ (st_row1 & 15)) << 4);
     const uint32_t st_v0 = st_row0 * 256 + ((st_ch ^ ((st_row0 & 3) << 2)) << 4);
     const uint32_t st_v1 = st_row1 * 256 + ((st_ch ^ ((st_row1 & 3) << 2)) << 4);
-    const int64_t kv_row_stride = (int64_t)a.Hkv * kHeadDim;          // elements
-    const uint16_t* kbase = a.k + (int64_t)kvh * kHeadDim + st_ch * 8;
-    const uint16_t* vbase = a.v + (int64_t)kvh * kHeadDim + st_ch * 8;
+    // global side: a uniform 64-bit base per tile (scalar registers) plus a per-thread 32-bit byte offset
+    // that never changes, so fetching a tile costs no vector address arithmetic
+    const uint32_t kv_row_bytes = (uint32_t)a.Hkv * kHeadDim * 2;
+    const uint32_t g_off0 = st_row0 * kv_row_bytes + st_ch * 16, g_off1 = st_row1 * kv_row_bytes + st_ch * 16;
+    const char* kreq = (const char*)a.k + ((int64_t)kv_lo * a.Hkv + kvh) * (kHeadDim * 2);   // row kv_lo, head kvh
+    const char* vreq = (const char*)a.v + ((int64_t)kv_lo * a.Hkv + kvh) * (kHeadDim * 2);
+    const int32_t* preq = a.kv_pos + kv_lo;
 
     // ---- operand read offsets
     // K (A operand of S^T): row 32*kvb + qi, chunk 2t + hi
@@ -214,16 +218,25 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
 
     uint4 gk0, gk1, gv0, gv1;
     int gpos = INT_MAX;
+    const int kv_len = kv_hi - kv_lo;
     auto load_tile = [&](int t) {
-        int r0 = kv_lo + t * kBN + st_row0, r1 = r0 + 32;
-        int c0 = min(r0, kv_hi - 1), c1 = min(r1, kv_hi - 1);
-        gk0 = *(const uint4*)(kbase + c0 * kv_row_stride);
-        gk1 = *(const uint4*)(kbase + c1 * kv_row_stride);
-        gv0 = *(const uint4*)(vbase + c0 * kv_row_stride);
-        gv1 = *(const uint4*)(vbase + c1 * kv_row_stride);
+        t = __builtin_amdgcn_readfirstlane(t);
+        const int64_t tile_off = (int64_t)t * kBN * kv_row_bytes;          // uniform
+        const char* kt = kreq + tile_off;
+        const char* vt = vreq + tile_off;
+        uint32_t o0 = g_off0, o1 = g_off1;
+        if (ragged_tail && t == nkt - 1) {    // rows past the end re-read the last row; their scores are masked
+            const int last = kv_len - 1 - t * kBN;
+            o0 = min(st_row0, last) * kv_row_bytes + st_ch * 16;
+            o1 = min(st_row1, last) * kv_row_bytes + st_ch * 16;
+        }
+        gk0 = *(const uint4*)(kt + o0);
+        gk1 = *(const uint4*)(kt + o1);
+        gv0 = *(const uint4*)(vt + o0);
+        gv1 = *(const uint4*)(vt + o1);
         if (tid < kBN) {
-            int r = kv_lo + t * kBN + tid;
-            gpos = r < kv_hi ? a.kv_pos[r] : INT_MAX;
+            int r = t * kBN + tid;
+            gpos = r < kv_len ? preq[r] : INT_MAX;
         }
     };
     auto store_tile = [&](int st) {
@@ -394,7 +407,11 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         // first fragments of the matrix phase: their tile has been in LDS for a whole iteration
 #pragma unroll
         for (int pb = 0; pb < 2; ++pb) read_batch(pb, pb, st_cur, st_nxt);
-        asm volatile("s_barrier" ::: "memory");    // nothing of this wavefront's LDS traffic is awaited by others
+        // the probabilities must be complete BEFORE the barrier (the compiler would otherwise sink the exp2
+        // work into the matrix phase, where it serialises with the MFMAs): the barrier consumes them
+        asm volatile("s_barrier"
+                     :: "v"(pf[0][0].v), "v"(pf[0][1].v), "v"(pf[1][0].v), "v"(pf[1][1].v), "v"(lsum)
+                     : "memory");                  // nothing of this wavefront's LDS traffic is awaited by others
         // ---- matrix phase: stage tile t_wr, prefetch the one after it, PV of t_cur, S of t_nxt
         // (after the last tile the S product runs on a stale stage and is discarded)
         if (t_wr < nkt) {
@@ -402,7 +419,10 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
             if (t_ld < nkt) load_tile(t_ld);
         }
         matrix_phase(0, 8, 2, st_cur, st_nxt);
-        lds_barrier();
+        // likewise every MFMA is issued before the phase ends
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier"
+                     :: "v"(sacc[0]), "v"(sacc[1]), "v"(oacc[0]), "v"(oacc[1]), "v"(oacc[2]), "v"(oacc[3])
+                     : "memory");
         t_cur = t_nxt; t_nxt = t_wr; t_wr = t_ld;
         mm_cur = mm_nxt; mm_nxt = mm_wr; mm_wr = mm_ld;
         st_cur = st_nxt;
