@@ -5,16 +5,25 @@
 //
 // Mapping to gfx950 (64-wide wavefronts, MFMA 32x32x16 bf16, 160 KiB LDS):
 //   * a workgroup of 8 wavefronts owns 256 query rows of one head; each wavefront owns 32 rows
-//     and keeps their Q fragment (B operand), running max / sum and the fp32 output
-//     accumulator in registers for the whole KV sweep;
-//   * K/V tiles of 64 rows go through LDS, double buffered; the K tile is the A operand of
-//     S^T = K Q^T, so a lane ends up with scores of ONE query row (its column) and the row
-//     statistics need one cross-half exchange only; P^T stays in registers and is the B operand
-//     of O^T = V^T P^T, whose A operand comes from transposing LDS reads of the row-major V tile;
-//   * 16-byte chunks are XOR-swizzled inside each 256-byte LDS row (differently for K and V) so
+//     and keeps their Q fragment (B operand), the softmax state and the fp32 output accumulator
+//     in registers for the whole KV sweep;
+//   * K/V tiles of 64 rows are fetched straight from global memory into a 4-stage LDS ring
+//     (global_load ... lds, no register staging), three tiles ahead of their use;
+//   * the K tile is the A operand of S^T = K Q^T, so a lane ends up with scores of ONE query
+//     row (its column); P^T stays in registers and is the B operand of O^T = V^T P^T, whose A
+//     operand comes from transposing LDS reads of the row-major V tile;
+//   * LDS rows of K are padded to 272 bytes and the 16-byte chunks of V rows are XOR-swizzled, so
 //     that the operand reads spread over all banks;
-//   * per (workgroup, KV tile) the minimum / maximum positions decide: tile hidden -> skipped
-//     without being loaded; tile fully visible -> no mask code; else element-wise kv_pos <= q_pos.
+//   * one instruction stream per wavefront, software pipelined: the MFMAs of S^T for tile j+1
+//     are interleaved with the exp2 / sum / bf16-pack work of tile j (a wavefront issues one
+//     instruction about every 8 cycles and a 32x32x16 MFMA lasts 32, so with two wavefronts per
+//     SIMD up to ~8 vector instructions fit behind every MFMA), then O^T += V^T P^T of tile j;
+//   * the softmax offset is refreshed only when needed (first visible key, or a probability sum
+//     that shows the offset has fallen more than 2^20 behind), so the common path has no max
+//     reduction and no rescale of the accumulator;
+//   * per (wavefront, KV tile) the minimum / maximum positions decide: tiles past the last one
+//     any row can see are never fetched; tiles below every row need no mask code; else the
+//     element-wise test kv_pos <= q_pos runs.
 #include <limits.h>
 
 #include "esp_common.h"
@@ -24,7 +33,9 @@ namespace esp {
 constexpr int kBM = 256;   // query rows per workgroup
 constexpr int kBN = 64;    // KV rows per tile
 constexpr int kPfWaves = 8;
-constexpr int kTileBytes = kBN * kHeadDim * 2;   // 16 KiB
+constexpr int kTileBytes = kBN * kHeadDim * 2;   // 16 KiB: a V tile in LDS, rows of 256 bytes
+constexpr int kKRow = 272;                       // LDS row pitch of a K tile: 256 bytes + 16 of padding
+constexpr int kKTileBytes = kBN * kKRow;         // 17 KiB = 17 transfers of 1 KiB
 
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4_t;
 #define ESP_LDS __attribute__((address_space(3)))
@@ -87,28 +98,38 @@ __device__ __forceinline__ float half_swap_sum(float x) {
     return lo + hi;
 }
 
-// LDS barrier that does not wait for outstanding global loads (the prefetch of a later tile stays
-// in flight across it): LDS traffic of this wavefront is drained, then the workgroup meets.
-__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+constexpr int kStages = 4;            // LDS stages per operand; tile j lives in stage j % 4
+constexpr float kSumLimit = 1048576.f;  // 2^20: a tile's probability sum above this refreshes the offset
 
-constexpr int kStages = 3;          // LDS stages per operand; tile j of the visible sequence lives in stage j % 3
-constexpr float kRescaleStep = 8.f; // the running max is refreshed only when it grows by more than 2^8
+#define ESP_GLOBAL __attribute__((address_space(1)))
 
-// Schedule inside a workgroup: the two wavefronts that share a SIMD (w and w + 4) run half an iteration
-// apart.  While one is in its matrix phase (O^T += V^T P^T of tile i, then S^T = K Q^T of tile i + 1) the
-// other is in its vector phase (mask, running max, exp2, row sum, bf16 pack of its tile), so the MFMA pipe
-// and the vector ALU of the SIMD are busy at the same time.  Phases are separated by workgroup barriers;
-// group B (wavefronts 4-7) passes one extra barrier before its loop and group A one after it.
+// One global -> LDS transfer of 64 x 16 bytes: lane L's 16 bytes (at gbase + voff) land at lds_addr + 16*L.
+// Issued as assembly so that the loads stay in flight across LDS reads of other stages; the matching
+// waits are the explicit vmcnt waits in the kernel.
+__device__ __forceinline__ void load_to_lds_b128(uint32_t lds_addr, const void* gbase, uint32_t voff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(voff), "s"(gbase) : "memory");
+}
+__device__ __forceinline__ void load_to_lds_b32(uint32_t lds_addr, const void* gbase, uint32_t voff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                 :: "s"(lds_addr), "v"(voff), "s"(gbase) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+template <int V> struct IC { static constexpr int value = V; };
+
 __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
-    __shared__ __attribute__((aligned(16))) unsigned char lds_k[kStages][kTileBytes];
-    __shared__ __attribute__((aligned(16))) unsigned char lds_v[kStages][kTileBytes];
-    __shared__ __attribute__((aligned(16))) int32_t lds_pos[kStages][kBN];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_k[kStages][kKTileBytes];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_v[kStages][kTileBytes];
+    __shared__ __attribute__((aligned(256))) int32_t lds_pos[kStages][kBN];
     __shared__ int32_t lds_qmm[2][kPfWaves];
+    __shared__ int32_t lds_sched[1 + kPfWaves];   // [0] last visible tile; [1 + w] first tile wavefront w must mask
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const bool group_b = wave >= kPfWaves / 2;
     const int G = a.Hq / a.Hkv;
 
     // ---- which (query tile, head): XCD-aware (consecutive workgroup ids land on consecutive
@@ -152,8 +173,9 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         kv_hi = a.cu_kv ? a.cu_kv[r + 1] : a.Tkv;
         tile0 = first_kv_tile;
     }
-    const int nkt = (kv_hi - kv_lo + kBN - 1) / kBN;
-    const bool ragged_tail = (kv_hi - kv_lo) % kBN != 0;
+    const int kv_len = kv_hi - kv_lo;
+    const int nkt = (kv_len + kBN - 1) / kBN;
+    const int tail_rows = kv_len - (nkt - 1) * kBN;    // rows of the last tile (64 when not ragged)
 
     // ---- this lane's query row (column of S^T) and its Q fragment
     const int qi = lane & 31, hi = lane >> 5;
@@ -166,8 +188,8 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
         for (int t = 0; t < 8; ++t) qf[t] = *(const bf16x8*)(qp + 16 * t);
     }
-    // effective query position: non-causal rows see every real key (the tail sentinel is INT_MAX)
-    const int my_qpos = a.causal ? a.q_pos[ld_row] : INT_MAX - 1;
+    // effective query position: non-causal rows see every key
+    const int my_qpos = a.causal ? a.q_pos[ld_row] : INT_MAX;
     int wave_qmin = my_qpos, wave_qmax = my_qpos;
 #pragma unroll
     for (int s = 16; s >= 1; s >>= 1) {
@@ -177,166 +199,194 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     wave_qmin = __builtin_amdgcn_readfirstlane(wave_qmin);
     wave_qmax = __builtin_amdgcn_readfirstlane(wave_qmax);
     if (lane == 0) { lds_qmm[0][wave] = wave_qmin; lds_qmm[1][wave] = wave_qmax; }
+    if (tid == 0) lds_sched[0] = -1;
+    if (tid < kPfWaves) lds_sched[1 + tid] = nkt;
     __syncthreads();
-    int wg_qmax = lds_qmm[1][0];
-#pragma unroll
-    for (int w = 1; w < kPfWaves; ++w) wg_qmax = max(wg_qmax, lds_qmm[1][w]);
-    wg_qmax = __builtin_amdgcn_readfirstlane(wg_qmax);
 
-    // ---- staging: thread -> two 16-byte chunks of the K tile and of the V tile
-    const int st_row0 = tid >> 4, st_row1 = st_row0 + 32, st_ch = tid & 15;
-    const uint32_t st_k0 = st_row0 * 256 + ((st_ch ^ (st_row0 & 15)) << 4);
-    const uint32_t st_k1 = st_row1 * 256 + ((st_ch ^ (st_row1 & 15)) << 4);
-    const uint32_t st_v0 = st_row0 * 256 + ((st_ch ^ ((st_row0 & 3) << 2)) << 4);
-    const uint32_t st_v1 = st_row1 * 256 + ((st_ch ^ ((st_row1 & 3) << 2)) << 4);
-    // global side: a uniform 64-bit base per tile (scalar registers) plus a per-thread 32-bit byte offset
-    // that never changes, so fetching a tile costs no vector address arithmetic
+    // ---- tile schedule of this workgroup: n_vis = 1 + last tile some row can see (tiles before it that are
+    //      hidden, possible only with unordered positions, are swept fully masked); first_mask = first tile
+    //      this wavefront has to mask (every later tile is masked too, which is exact for ascending positions
+    //      and merely redundant otherwise)
+    int n_vis = nkt, first_mask = nkt;
+    if (a.causal) {
+        int wg_qmax = lds_qmm[1][0];
+#pragma unroll
+        for (int w = 1; w < kPfWaves; ++w) wg_qmax = max(wg_qmax, lds_qmm[1][w]);
+        int last_vis = -1, fm[kPfWaves];
+#pragma unroll
+        for (int w = 0; w < kPfWaves; ++w) fm[w] = nkt;
+        for (int t = tid; t < nkt; t += kPfWaves * 64) {
+            const int2 mm = a.tile_mm[tile0 + t];
+            if (mm.x <= wg_qmax) last_vis = max(last_vis, t);
+#pragma unroll
+            for (int w = 0; w < kPfWaves; ++w)
+                if (mm.y > lds_qmm[0][w]) fm[w] = min(fm[w], t);
+        }
+        if (last_vis >= 0) atomicMax(&lds_sched[0], last_vis);
+#pragma unroll
+        for (int w = 0; w < kPfWaves; ++w)
+            if (fm[w] < nkt) atomicMin(&lds_sched[1 + w], fm[w]);
+        __syncthreads();
+        n_vis = __builtin_amdgcn_readfirstlane(lds_sched[0]) + 1;
+        first_mask = __builtin_amdgcn_readfirstlane(lds_sched[1 + wave]);
+    }
+
+    // ---- global -> LDS in transfers of 64 lanes x 16 bytes = 1 KiB of consecutive LDS bytes.
+    //      V tile (rows of 256 B, chunks XOR-swizzled): wavefront w moves rows 8w .. 8w+7 in two transfers; lane L
+    //      writes LDS chunk L % 16 of row r = base + L / 16, so it fetches the global chunk (L % 16) ^ f(r).
+    //      K tile (rows padded to 272 B): transfer n covers LDS bytes [1024 n, 1024 n + 1024) of the padded tile;
+    //      lane L's byte 1024 n + 16 L falls into row B / 272 at B % 272 (a padding slot fetches chunk 0, unused).
+    //      Wavefront w issues K transfers w and w + 8; wavefront 7 also the 17th; wavefront 0 the positions.
     const uint32_t kv_row_bytes = (uint32_t)a.Hkv * kHeadDim * 2;
-    const uint32_t g_off0 = st_row0 * kv_row_bytes + st_ch * 16, g_off1 = st_row1 * kv_row_bytes + st_ch * 16;
+    const int st_sub = lane >> 4, st_p = lane & 15;
+    const int st_r0 = wave * 8 + st_sub, st_r1 = st_r0 + 4;
+    auto v_goff = [&](int r_lds, int r_glb) { return r_glb * kv_row_bytes + ((st_p ^ ((r_lds & 3) << 2)) << 4); };
+    auto k_goff = [&](int n, int last_row) {
+        const int B = 1024 * n + 16 * lane, row = B / kKRow, within = B - row * kKRow;
+        return (uint32_t)(min(row, last_row) * kv_row_bytes + (within < 256 ? within : 0));
+    };
+    const uint32_t gv0 = v_goff(st_r0, st_r0), gv1 = v_goff(st_r1, st_r1);
+    const uint32_t gk0 = k_goff(wave, kBN - 1), gk1 = k_goff(wave + 8, kBN - 1), gk2 = k_goff(16, kBN - 1);
     const char* kreq = (const char*)a.k + ((int64_t)kv_lo * a.Hkv + kvh) * (kHeadDim * 2);   // row kv_lo, head kvh
     const char* vreq = (const char*)a.v + ((int64_t)kv_lo * a.Hkv + kvh) * (kHeadDim * 2);
     const int32_t* preq = a.kv_pos + kv_lo;
+    const uint32_t lds_k0 = (uint32_t)(uintptr_t)(ESP_LDS unsigned char*)&lds_k[0][0];
+    const uint32_t lds_v0 = (uint32_t)(uintptr_t)(ESP_LDS unsigned char*)&lds_v[0][0];
+    const uint32_t lds_p0 = (uint32_t)(uintptr_t)(ESP_LDS int32_t*)&lds_pos[0][0];
+
+    // fetch tile t into stage st (5 transfers for wavefronts 0 and 7, 4 for the others)
+    auto fetch_tile = [&](int t, int st) {
+        t = __builtin_amdgcn_readfirstlane(t);
+        const int64_t tile_off = (int64_t)t * kBN * kv_row_bytes;          // uniform
+        const char* kt = kreq + tile_off;
+        const char* vt = vreq + tile_off;
+        uint32_t k0 = gk0, k1 = gk1, k2 = gk2, v0 = gv0, v1 = gv1, po = lane * 4;
+        if (t == nkt - 1 && tail_rows < kBN) {   // rows past the end re-read the last row; their scores get masked
+            const int last = tail_rows - 1;
+            k0 = k_goff(wave, last); k1 = k_goff(wave + 8, last); k2 = k_goff(16, last);
+            v0 = v_goff(st_r0, min(st_r0, last)); v1 = v_goff(st_r1, min(st_r1, last));
+            po = min(lane, last) * 4;
+        }
+        const uint32_t ko = lds_k0 + st * kKTileBytes, vo = lds_v0 + st * kTileBytes + wave * 2048;
+        load_to_lds_b128(ko + 1024 * wave, kt, k0);
+        load_to_lds_b128(ko + 1024 * (wave + 8), kt, k1);
+        load_to_lds_b128(vo, vt, v0);
+        load_to_lds_b128(vo + 1024, vt, v1);
+        if (wave == 7) load_to_lds_b128(ko + 1024 * 16, kt, k2);
+        if (wave == 0) load_to_lds_b32(lds_p0 + st * (kBN * 4), preq + t * kBN, po);
+    };
 
     // ---- operand read offsets
-    // K (A operand of S^T): row 32*kvb + qi, chunk 2t + hi
-    const uint32_t k_row = qi * 256, k_x = qi & 15;
-    auto k_rd = [&](int t) { return k_row + (((2 * t + hi) ^ k_x) << 4); };
+    // K (A operand of S^T): row 32*kvb + qi, chunk 2t + hi -> one base per lane, the rest are immediates
+    const uint32_t k_rd = qi * kKRow + hi * 16;
     // V (A operand of O^T) by transposing reads: 16 lanes fetch a 4 (kv) x 16 (d) patch
-    const int j = lane & 15, jq = j >> 2, dblk = (lane >> 4) & 1;
+    const int j16 = lane & 15, jq = j16 >> 2, dblk = (lane >> 4) & 1;
     uint32_t v_rd[4];
 #pragma unroll
     for (int db = 0; db < 4; ++db)
-        v_rd[db] = (4 * hi + jq) * 256 + ((((db ^ jq) << 2) + 2 * dblk + ((j & 3) >> 1)) << 4) + (j & 1) * 8;
+        v_rd[db] = (4 * hi + jq) * 256 + ((((db ^ jq) << 2) + 2 * dblk + ((j16 & 3) >> 1)) << 4) + (j16 & 1) * 8;
 
     floatx16 oacc[4];
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
-    float m_ref = -INFINITY;   // exponent offset in use (scale*log2(e)*score units); trails the true max by <= 2^8
+    float m_ref = -INFINITY;   // softmax offset in use (scale*log2(e)*score units), the same in both halves
     float lsum = 0.f;          // running sum of exp2 over this lane's half of the keys
 
-    uint4 gk0, gk1, gv0, gv1;
-    int gpos = INT_MAX;
-    const int kv_len = kv_hi - kv_lo;
-    auto load_tile = [&](int t) {
-        t = __builtin_amdgcn_readfirstlane(t);
-        const int64_t tile_off = (int64_t)t * kBN * kv_row_bytes;          // uniform
-        const char* kt = kreq + tile_off;
-        const char* vt = vreq + tile_off;
-        uint32_t o0 = g_off0, o1 = g_off1;
-        if (ragged_tail && t == nkt - 1) {    // rows past the end re-read the last row; their scores are masked
-            const int last = kv_len - 1 - t * kBN;
-            o0 = min(st_row0, last) * kv_row_bytes + st_ch * 16;
-            o1 = min(st_row1, last) * kv_row_bytes + st_ch * 16;
-        }
-        gk0 = *(const uint4*)(kt + o0);
-        gk1 = *(const uint4*)(kt + o1);
-        gv0 = *(const uint4*)(vt + o0);
-        gv1 = *(const uint4*)(vt + o1);
-        if (tid < kBN) {
-            int r = t * kBN + tid;
-            gpos = r < kv_len ? preq[r] : INT_MAX;
-        }
-    };
-    auto store_tile = [&](int st) {
-        *(uint4*)(lds_k[st] + st_k0) = gk0;
-        *(uint4*)(lds_k[st] + st_k1) = gk1;
-        *(uint4*)(lds_v[st] + st_v0) = gv0;
-        *(uint4*)(lds_v[st] + st_v1) = gv1;
-        if (tid < kBN) lds_pos[st][tid] = gpos;
-    };
-
-    floatx16 sacc[2];          // S^T of the tile in flight, then its probabilities
+    floatx16 sbuf[2][2];       // S^T of two tiles in flight: [tile parity][kvb]
     union PFrag { uint32_t u[4]; bf16x8 v; };
-    PFrag pf[2][2];            // P^T packed to bf16: [kvb][t2]
-    // per-tile facts, wavefront-uniform, from the tile's (min, max) position
-    auto tile_needs_mask = [&](int t, int2 mm) {
-        return (ragged_tail && t == nkt - 1) || (a.causal && mm.y > wave_qmin);
+    PFrag pf[2][2];            // P^T of the current tile packed to bf16: [kvb][t2]
+    union VFrag { short4_t s[2]; bf16x8 v; };
+    constexpr int kRing = 5;
+    VFrag fr[kRing];           // ring of operand fragments, fetched kRing MFMAs ahead of their use
+
+    // The 32 MFMAs of an iteration: m = 0..15 is S^T = K Q^T of the next tile, (t, kvb) = (m / 2, m % 2);
+    // m = 16..31 is O^T += V^T P^T of the current tile, (kvb, t2, db) = ((m-16) / 8, ((m-16) / 4) % 2, m % 4).
+    auto read_frag = [&](int m, int st_k, int st_v) {
+        if (m < 16) {
+            const int t = m >> 1, kvb = m & 1;
+            fr[m % kRing].v = *(const bf16x8*)(lds_k[st_k] + kvb * (32 * kKRow) + t * 32 + k_rd);
+        } else {
+            const int kvb = (m - 16) >> 3, t2 = ((m - 16) >> 2) & 1, db = m & 3;
+            const unsigned char* vp = lds_v[st_v] + (32 * kvb + 16 * t2) * 256 + v_rd[db];
+            fr[m % kRing].s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ESP_LDS short4_t*)(vp));
+            fr[m % kRing].s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ESP_LDS short4_t*)(vp + 8 * 256));
+        }
     };
 
-    // Operand fragments are fetched from LDS in batches of four MFMAs, two batches ahead of their use,
-    // so that the LDS latency hides behind the MFMAs of earlier batches.  Batches 0-3: V^T fragments of
-    // O^T += V^T P^T (two transposing reads each); batches 4-7: K fragments of S^T = K Q^T.
-    union VFrag { short4_t s[2]; bf16x8 v; };
-    VFrag fr[2][4];
-    auto read_batch = [&](int bi, int slot, int st_v, int st_k) {
-        if (bi < 4) {
-            const int kvb = bi >> 1, t2 = bi & 1;
+    // mask of tile j (positions in lds_pos[st]; rows of a ragged last tile past `valid` are hidden too)
+    auto apply_mask = [&](floatx16 (&sc)[2], int st, int valid) {
+        const int lim = valid - 4 * hi;
 #pragma unroll
-            for (int db = 0; db < 4; ++db) {
-                const unsigned char* vp = lds_v[st_v] + (32 * kvb + 16 * t2) * 256 + v_rd[db];
-                fr[slot][db].s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ESP_LDS short4_t*)(vp));
-                fr[slot][db].s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ESP_LDS short4_t*)(vp + 8 * 256));
-            }
-        } else {
-            const int tp = bi - 4;   // t = 2*tp, 2*tp + 1
+        for (int kvb = 0; kvb < 2; ++kvb)
 #pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int t = 2 * tp + (x >> 1), kvb = x & 1;
-                fr[slot][x].v = *(const bf16x8*)(lds_k[st_k] + kvb * 8192 + k_rd(t));
+            for (int bb = 0; bb < 4; ++bb) {
+                const int4 kp = *(const int4*)(&lds_pos[st][32 * kvb + 8 * bb + 4 * hi]);
+                const int base = 32 * kvb + 8 * bb;
+                if (kp.x > my_qpos || base + 0 >= lim) sc[kvb][4 * bb + 0] = -INFINITY;
+                if (kp.y > my_qpos || base + 1 >= lim) sc[kvb][4 * bb + 1] = -INFINITY;
+                if (kp.z > my_qpos || base + 2 >= lim) sc[kvb][4 * bb + 2] = -INFINITY;
+                if (kp.w > my_qpos || base + 3 >= lim) sc[kvb][4 * bb + 3] = -INFINITY;
             }
-        }
     };
-    auto mfma_batch = [&](int bi, int slot) {
-        if (bi < 4) {
-            const int kvb = bi >> 1, t2 = bi & 1;
-#pragma unroll
-            for (int db = 0; db < 4; ++db)
-                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[slot][db].v, pf[kvb][t2].v, oacc[db], 0, 0, 0);
-        } else {
-            const int tp = bi - 4;
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int t = 2 * tp + (x >> 1), kvb = x & 1;
-                sacc[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[slot][x].v, qf[t], sacc[kvb], 0, 0, 0);
-            }
-        }
+
+    float psum, m_use;
+    // probabilities of score pair c (0..15) of the current tile: exp2, partial sum, bf16 pack
+    auto prob_pair = [&](const floatx16 (&sc)[2], int c) {
+        const int kvb = c >> 3, r = 2 * (c & 7);
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[kvb][r], a.scale_log2, -m_use));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[kvb][r + 1], a.scale_log2, -m_use));
+        psum += p0;
+        psum += p1;
+        pf[kvb][(c & 7) >> 2].u[c & 3] = pack_bf16(p0, p1);
     };
-    // runs batches [first, last); the fragments of the first `primed` batches are already in flight
-    auto matrix_phase = [&](int first, int last, int primed, int st_v, int st_k) {
+
+    // one tile: softmax of tile j (scores in sbuf[PAR]) interleaved with S^T of tile j+1 (into sbuf[PAR^1]),
+    // then O^T += V^T P^T of tile j; fetch of tile j+3
+    auto iteration = [&](auto st_c, auto par_c, int j) {
+        constexpr int ST = decltype(st_c)::value, PAR = decltype(par_c)::value;
+        constexpr int ST1 = (ST + 1) % kStages, ST3 = (ST + 3) % kStages;
+        floatx16 (&sc)[2] = sbuf[PAR];
+        floatx16 (&sn)[2] = sbuf[PAR ^ 1];
+        const bool fetch = j + 3 < n_vis;
+        if (fetch) fetch_tile(j + 3, ST3);            // stage ST3 held tile j-1: free since the last barrier
+        if (j >= first_mask || (j == nkt - 1 && tail_rows < kBN)) apply_mask(sc, ST, j == nkt - 1 ? tail_rows : kBN);
+        m_use = (m_ref == -INFINITY) ? 0.f : m_ref;
+        psum = 0.f;
 #pragma unroll
-        for (int bi = first; bi < last; ++bi) {
-            if (bi == first) {
+        for (int m = 0; m < kRing; ++m) read_frag(m, ST1, ST);
+        __builtin_amdgcn_sched_barrier(0);
+        // a few probability pairs first: they cover the latency of the first fragment reads
+        prob_pair(sc, 0);
+        prob_pair(sc, 1);
+        prob_pair(sc, 2);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int pb = first + primed; pb < first + 2 && pb < last; ++pb) read_batch(pb, pb % 2, st_v, st_k);
-                __builtin_amdgcn_sched_barrier(0);
+        for (int m = 0; m < 16; ++m) {                // S^T of tile j+1 (after the last tile: stale data, unused)
+            const int t = m >> 1, kvb = m & 1;
+            if (t == 0) {
+                floatx16 zero;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+                sn[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[m % kRing].v, qf[t], zero, 0, 0, 0);
+            } else {
+                sn[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[m % kRing].v, qf[t], sn[kvb], 0, 0, 0);
             }
-            if (bi == 4)
-#pragma unroll
-                for (int kvb = 0; kvb < 2; ++kvb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) sacc[kvb][r] = 0.f;
-            mfma_batch(bi, bi % 2);
-            if (bi + 2 < last) read_batch(bi + 2, bi % 2, st_v, st_k);
+            read_frag(m + kRing, ST1, ST);            // the slot is free again
+            if (m < 13) prob_pair(sc, m + 3);
             __builtin_amdgcn_sched_barrier(0);
         }
-    };
-
-    auto softmax = [&](int st, bool need_mask) {
-        if (need_mask) {
+        // offset refresh (rare): first visible key of a row, or a sum that shows the offset fell far behind
+        const bool redo = (m_ref == -INFINITY) || !(psum <= kSumLimit);
+        if (__builtin_amdgcn_ballot_w64(redo) != 0) {
+            float tmax = sc[0][0];
 #pragma unroll
-            for (int kvb = 0; kvb < 2; ++kvb)
+            for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, sc[0][r]);
 #pragma unroll
-                for (int bb = 0; bb < 4; ++bb) {
-                    int4 kp = *(const int4*)(&lds_pos[st][32 * kvb + 8 * bb + 4 * hi]);
-                    if (kp.x > my_qpos) sacc[kvb][4 * bb + 0] = -INFINITY;
-                    if (kp.y > my_qpos) sacc[kvb][4 * bb + 1] = -INFINITY;
-                    if (kp.z > my_qpos) sacc[kvb][4 * bb + 2] = -INFINITY;
-                    if (kp.w > my_qpos) sacc[kvb][4 * bb + 3] = -INFINITY;
-                }
-        }
-        float tmax = sacc[0][0];
-#pragma unroll
-        for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, sacc[0][r]);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sacc[1][r]);
-        tmax = half_swap_max(tmax) * a.scale_log2;
-        // refresh the exponent offset only when the row max outgrew it by more than 2^8 (or at the first
-        // visible key): probabilities stay <= 2^8, which bf16 and the fp32 sums hold without loss
-        const bool grow = tmax > m_ref + kRescaleStep;   // false while everything is still hidden (-inf > -inf)
-        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-            const float m_new = grow ? tmax : m_ref;
+            for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sc[1][r]);
+            tmax = half_swap_max(tmax) * a.scale_log2;
+            const float m_new = fmaxf(m_ref, tmax);
             const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_ref - m_new);
             m_ref = m_new;
             lsum *= alpha;
@@ -344,90 +394,54 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
             for (int db = 0; db < 4; ++db)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+            m_use = (m_ref == -INFINITY) ? 0.f : m_ref;   // still nothing visible: exp2(-inf - 0) = 0
+            psum = 0.f;
+#pragma unroll
+            for (int c = 0; c < 16; ++c) prob_pair(sc, c);
         }
-        const float m_use = (m_ref == -INFINITY) ? 0.f : m_ref;   // all keys hidden so far: exp2(-inf - 0) = 0
-        float psum = 0.f;
-#pragma unroll
-        for (int kvb = 0; kvb < 2; ++kvb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float p = __builtin_amdgcn_exp2f(fmaf(sacc[kvb][r], a.scale_log2, -m_use));
-                sacc[kvb][r] = p;
-                psum += p;
-            }
         lsum += psum;
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int kvb = 0; kvb < 2; ++kvb)
-#pragma unroll
-            for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    pf[kvb][t2].u[e] = pack_bf16(sacc[kvb][8 * t2 + 2 * e], sacc[kvb][8 * t2 + 2 * e + 1]);
-    };
-
-    // ---- sequence of visible tiles (skipping tiles no row of the workgroup can see), with their (min, max)
-    auto tile_mm_at = [&](int t) {
-        const int2* p = a.tile_mm + __builtin_amdgcn_readfirstlane(tile0 + t);   // uniform: a scalar load
-        return *p;
-    };
-    auto next_tile = [&](int t, int2& mm) {
-        mm = make_int2(0, 0);
-        if (a.causal) {
-            while (t < nkt) {
-                mm = tile_mm_at(t);
-                if (mm.x <= wg_qmax) break;
-                ++t;
-            }
+        for (int m = 16; m < 32; ++m) {               // O^T += V^T P^T of tile j
+            const int kvb = (m - 16) >> 3, t2 = ((m - 16) >> 2) & 1, db = m & 3;
+            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[m % kRing].v, pf[kvb][t2].v, oacc[db], 0, 0, 0);
+            if (m + kRing < 32) read_frag(m + kRing, ST1, ST);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        return t;
-    };
-
-    // ---- prologue: tiles 0 and 1 of the visible sequence into LDS, tile 2 into registers, S of tile 0
-    // (a wavefront whose 32 rows cannot see a tile still runs it, fully masked: it would only wait at the
-    //  barriers otherwise, and one straight-line loop body keeps the register allocation tight)
-    int2 mm_cur, mm_nxt, mm_wr, mm_ld = make_int2(0, 0);
-    int t_cur = next_tile(0, mm_cur);                                   // tile whose S is in sacc / P in pf
-    int t_nxt = t_cur < nkt ? next_tile(t_cur + 1, mm_nxt) : nkt;       // tile of the next S
-    int t_wr = t_nxt < nkt ? next_tile(t_nxt + 1, mm_wr) : nkt;         // tile in registers, next to enter LDS
-    if (t_cur < nkt) { load_tile(t_cur); store_tile(0); }
-    if (t_nxt < nkt) { load_tile(t_nxt); store_tile(1); }
-    if (t_wr < nkt) load_tile(t_wr);
-    lds_barrier();
-    if (t_cur < nkt) matrix_phase(4, 8, 0, 0, 0);
-    if (group_b) lds_barrier();
-
-    int st_cur = 0;                                // LDS stage of t_cur
-    while (t_cur < nkt) {
-        // ---- vector phase: softmax of tile t_cur; bookkeeping of the tile to prefetch
-        const int st_nxt = st_cur == kStages - 1 ? 0 : st_cur + 1;
-        const int st_wr = st_nxt == kStages - 1 ? 0 : st_nxt + 1;
-        int t_ld = nkt;
-        if (t_wr < nkt) t_ld = next_tile(t_wr + 1, mm_ld);
-        softmax(st_cur, tile_needs_mask(t_cur, mm_cur));
-        // first fragments of the matrix phase: their tile has been in LDS for a whole iteration
-#pragma unroll
-        for (int pb = 0; pb < 2; ++pb) read_batch(pb, pb, st_cur, st_nxt);
-        // the probabilities must be complete BEFORE the barrier (the compiler would otherwise sink the exp2
-        // work into the matrix phase, where it serialises with the MFMAs): the barrier consumes them
-        asm volatile("s_barrier"
-                     :: "v"(pf[0][0].v), "v"(pf[0][1].v), "v"(pf[1][0].v), "v"(pf[1][1].v), "v"(lsum)
-                     : "memory");                  // nothing of this wavefront's LDS traffic is awaited by others
-        // ---- matrix phase: stage tile t_wr, prefetch the one after it, PV of t_cur, S of t_nxt
-        // (after the last tile the S product runs on a stale stage and is discarded)
-        if (t_wr < nkt) {
-            store_tile(st_wr);
-            if (t_ld < nkt) load_tile(t_ld);
-        }
-        matrix_phase(0, 8, 2, st_cur, st_nxt);
-        // likewise every MFMA is issued before the phase ends
+        // tile j+2 (fetched during iteration j-1) must have landed before the barrier publishes it; the
+        // transfers of tile j+3 issued above may stay in flight
+        if (fetch) { if (wave == 0 || wave == 7) wait_vm<5>(); else wait_vm<4>(); }
+        else wait_vm<0>();
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier"
-                     :: "v"(sacc[0]), "v"(sacc[1]), "v"(oacc[0]), "v"(oacc[1]), "v"(oacc[2]), "v"(oacc[3])
-                     : "memory");
-        t_cur = t_nxt; t_nxt = t_wr; t_wr = t_ld;
-        mm_cur = mm_nxt; mm_nxt = mm_wr; mm_wr = mm_ld;
-        st_cur = st_nxt;
+                     :: "v"(sn[0]), "v"(sn[1]), "v"(oacc[0]), "v"(oacc[1]), "v"(oacc[2]), "v"(oacc[3]) : "memory");
+    };
+
+    // ---- prologue: tiles 0..2 into LDS, S^T of tile 0
+    if (n_vis > 0) fetch_tile(0, 0);
+    if (n_vis > 1) fetch_tile(1, 1);
+    if (n_vis > 2) fetch_tile(2, 2);
+    wait_vm<0>();
+    wg_barrier();
+    if (n_vis > 0) {
+#pragma unroll
+        for (int m = 0; m < kRing; ++m) read_frag(m, 0, 0);
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+            const int t = m >> 1, kvb = m & 1;
+            if (t == 0) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sbuf[0][kvb][r] = 0.f;
+            }
+            sbuf[0][kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[m % kRing].v, qf[t], sbuf[0][kvb], 0, 0, 0);
+            if (m + kRing < 16) read_frag(m + kRing, 0, 0);
+        }
     }
-    if (!group_b) lds_barrier();
+    for (int j = 0; j < n_vis;) {
+        iteration(IC<0>{}, IC<0>{}, j); if (++j >= n_vis) break;
+        iteration(IC<1>{}, IC<1>{}, j); if (++j >= n_vis) break;
+        iteration(IC<2>{}, IC<0>{}, j); if (++j >= n_vis) break;
+        iteration(IC<3>{}, IC<1>{}, j); ++j;
+    }
 
     // ---- epilogue: normalise, write O (bf16) and LSE (natural log)
     const float ltot = half_swap_sum(lsum);
