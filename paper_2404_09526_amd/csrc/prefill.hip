@@ -188,8 +188,8 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
         for (int t = 0; t < 8; ++t) qf[t] = *(const bf16x8*)(qp + 16 * t);
     }
-    // effective query position: non-causal rows see every key
-    const int my_qpos = a.causal ? a.q_pos[ld_row] : INT_MAX;
+    // effective query position: non-causal rows see every real key
+    const int my_qpos = a.causal ? a.q_pos[ld_row] : INT_MAX - 1;   // INT_MAX marks rows past a ragged tail
     int wave_qmin = my_qpos, wave_qmax = my_qpos;
 #pragma unroll
     for (int s = 16; s >= 1; s >>= 1) {
@@ -254,26 +254,53 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     const uint32_t lds_v0 = (uint32_t)(uintptr_t)(ESP_LDS unsigned char*)&lds_v[0][0];
     const uint32_t lds_p0 = (uint32_t)(uintptr_t)(ESP_LDS int32_t*)&lds_pos[0][0];
 
-    // fetch tile t into stage st (5 transfers for wavefronts 0 and 7, 4 for the others)
-    auto fetch_tile = [&](int t, int st) {
+    // K of tile t into K stage st: 2 transfers per wavefront, 3 for wavefront 7
+    auto fetch_k = [&](int t, int st) {
         t = __builtin_amdgcn_readfirstlane(t);
-        const int64_t tile_off = (int64_t)t * kBN * kv_row_bytes;          // uniform
-        const char* kt = kreq + tile_off;
-        const char* vt = vreq + tile_off;
-        uint32_t k0 = gk0, k1 = gk1, k2 = gk2, v0 = gv0, v1 = gv1, po = lane * 4;
+        const char* kt = kreq + (int64_t)t * kBN * kv_row_bytes;          // uniform
+        const uint32_t ko = lds_k0 + st * kKTileBytes;
         if (t == nkt - 1 && tail_rows < kBN) {   // rows past the end re-read the last row; their scores get masked
             const int last = tail_rows - 1;
-            k0 = k_goff(wave, last); k1 = k_goff(wave + 8, last); k2 = k_goff(16, last);
-            v0 = v_goff(st_r0, min(st_r0, last)); v1 = v_goff(st_r1, min(st_r1, last));
-            po = min(lane, last) * 4;
+            load_to_lds_b128(ko + 1024 * wave, kt, k_goff(wave, last));
+            load_to_lds_b128(ko + 1024 * (wave + 8), kt, k_goff(wave + 8, last));
+            if (wave == 7) load_to_lds_b128(ko + 1024 * 16, kt, k_goff(16, last));
+        } else {
+            load_to_lds_b128(ko + 1024 * wave, kt, gk0);
+            load_to_lds_b128(ko + 1024 * (wave + 8), kt, gk1);
+            if (wave == 7) load_to_lds_b128(ko + 1024 * 16, kt, gk2);
         }
-        const uint32_t ko = lds_k0 + st * kKTileBytes, vo = lds_v0 + st * kTileBytes + wave * 2048;
-        load_to_lds_b128(ko + 1024 * wave, kt, k0);
-        load_to_lds_b128(ko + 1024 * (wave + 8), kt, k1);
-        load_to_lds_b128(vo, vt, v0);
-        load_to_lds_b128(vo + 1024, vt, v1);
-        if (wave == 7) load_to_lds_b128(ko + 1024 * 16, kt, k2);
-        if (wave == 0) load_to_lds_b32(lds_p0 + st * (kBN * 4), preq + t * kBN, po);
+    };
+    // V and positions of tile t into V stage st: 2 transfers per wavefront, 3 for wavefront 0
+    auto fetch_v = [&](int t, int st) {
+        t = __builtin_amdgcn_readfirstlane(t);
+        const char* vt = vreq + (int64_t)t * kBN * kv_row_bytes;
+        const uint32_t vo = lds_v0 + st * kTileBytes + wave * 2048;
+        if (t == nkt - 1 && tail_rows < kBN) {
+            const int last = tail_rows - 1;
+            load_to_lds_b128(vo, vt, v_goff(st_r0, min(st_r0, last)));
+            load_to_lds_b128(vo + 1024, vt, v_goff(st_r1, min(st_r1, last)));
+            if (wave == 0) load_to_lds_b32(lds_p0 + st * (kBN * 4), preq + t * kBN, min(lane, last) * 4);
+        } else {
+            load_to_lds_b128(vo, vt, gv0);
+            load_to_lds_b128(vo + 1024, vt, gv1);
+            if (wave == 0) load_to_lds_b32(lds_p0 + st * (kBN * 4), preq + t * kBN, lane * 4);
+        }
+    };
+    // transfers in flight that may stay in flight at the end of an iteration: the ones it issued itself
+    auto wait_older_than = [&](bool did_k, bool did_v) {
+        const int n = (did_k ? 2 + (wave == 7) : 0) + (did_v ? 2 + (wave == 0) : 0);
+        switch (n) {
+            case 5: wait_vm<5>(); break;
+            case 4: wait_vm<4>(); break;
+            case 3: wait_vm<3>(); break;
+            case 2: wait_vm<2>(); break;
+            default: wait_vm<0>(); break;
+        }
+    };
+    // positions past the end of a ragged last tile become INT_MAX, hidden from every query
+    auto seal_tail = [&](int st) {
+        if (wave == 0 && lane >= tail_rows) lds_pos[st][lane] = INT_MAX;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // written before the barrier that follows
     };
 
     // ---- operand read offsets
@@ -298,15 +325,16 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     union PFrag { uint32_t u[4]; bf16x8 v; };
     PFrag pf[2][2];            // P^T of the current tile packed to bf16: [kvb][t2]
     union VFrag { short4_t s[2]; bf16x8 v; };
-    constexpr int kRing = 5;
+    constexpr int kRing = 4;
     VFrag fr[kRing];           // ring of operand fragments, fetched kRing MFMAs ahead of their use
 
     // The 32 MFMAs of an iteration: m = 0..15 is S^T = K Q^T of the next tile, (t, kvb) = (m / 2, m % 2);
-    // m = 16..31 is O^T += V^T P^T of the current tile, (kvb, t2, db) = ((m-16) / 8, ((m-16) / 4) % 2, m % 4).
-    auto read_frag = [&](int m, int st_k, int st_v) {
-        if (m < 16) {
-            const int t = m >> 1, kvb = m & 1;
-            fr[m % kRing].v = *(const bf16x8*)(lds_k[st_k] + kvb * (32 * kKRow) + t * 32 + k_rd);
+    // m = 16..31 is O^T += V^T P^T of the current tile, (kvb, t2, db) = ((m-16) / 8, ((m-16) / 4) % 2, m % 4);
+    // m = 32..35 are the first fragments of the following iteration (K of the tile after next).
+    auto read_frag = [&](int m, int st_k, int st_k2, int st_v) {
+        if (m < 16 || m >= 32) {
+            const int mm = m & 15, t = mm >> 1, kvb = mm & 1;
+            fr[m % kRing].v = *(const bf16x8*)(lds_k[m < 16 ? st_k : st_k2] + kvb * (32 * kKRow) + t * 32 + k_rd);
         } else {
             const int kvb = (m - 16) >> 3, t2 = ((m - 16) >> 2) & 1, db = m & 3;
             const unsigned char* vp = lds_v[st_v] + (32 * kvb + 16 * t2) * 256 + v_rd[db];
@@ -315,19 +343,17 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         }
     };
 
-    // mask of tile j (positions in lds_pos[st]; rows of a ragged last tile past `valid` are hidden too)
-    auto apply_mask = [&](floatx16 (&sc)[2], int st, int valid) {
-        const int lim = valid - 4 * hi;
+    // mask of tile j: key positions in lds_pos[st] against this lane's query position
+    auto apply_mask = [&](floatx16 (&sc)[2], int st) {
 #pragma unroll
         for (int kvb = 0; kvb < 2; ++kvb)
 #pragma unroll
             for (int bb = 0; bb < 4; ++bb) {
                 const int4 kp = *(const int4*)(&lds_pos[st][32 * kvb + 8 * bb + 4 * hi]);
-                const int base = 32 * kvb + 8 * bb;
-                if (kp.x > my_qpos || base + 0 >= lim) sc[kvb][4 * bb + 0] = -INFINITY;
-                if (kp.y > my_qpos || base + 1 >= lim) sc[kvb][4 * bb + 1] = -INFINITY;
-                if (kp.z > my_qpos || base + 2 >= lim) sc[kvb][4 * bb + 2] = -INFINITY;
-                if (kp.w > my_qpos || base + 3 >= lim) sc[kvb][4 * bb + 3] = -INFINITY;
+                if (kp.x > my_qpos) sc[kvb][4 * bb + 0] = -INFINITY;
+                if (kp.y > my_qpos) sc[kvb][4 * bb + 1] = -INFINITY;
+                if (kp.z > my_qpos) sc[kvb][4 * bb + 2] = -INFINITY;
+                if (kp.w > my_qpos) sc[kvb][4 * bb + 3] = -INFINITY;
             }
     };
 
@@ -342,26 +368,20 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         pf[kvb][(c & 7) >> 2].u[c & 3] = pack_bf16(p0, p1);
     };
 
-    // one tile: softmax of tile j (scores in sbuf[PAR]) interleaved with S^T of tile j+1 (into sbuf[PAR^1]),
-    // then O^T += V^T P^T of tile j; fetch of tile j+3
+    // One tile.  On entry: scores of tile j in sbuf[PAR], the first kRing K fragments of tile j+1 in fr.
+    // The exp2 work of tile j is interleaved with S^T of tile j+1 (into sbuf[PAR^1]); then O^T += V^T P^T of
+    // tile j, with the fetch of K(j+4), V(j+3) and the first K fragments of tile j+2 issued among its MFMAs.
+    // LDS stages: K(t), V(t) and the positions of tile t live in stage t % 4.  K(j) is dead during iteration j
+    // (S^T of tile j was finished before the previous barrier), so K(j+4) may overwrite it; V(j+3) overwrites
+    // V(j-1).  What iteration j-1 fetched has landed before the barrier that ends iteration j.
     auto iteration = [&](auto st_c, auto par_c, int j) {
         constexpr int ST = decltype(st_c)::value, PAR = decltype(par_c)::value;
-        constexpr int ST1 = (ST + 1) % kStages, ST3 = (ST + 3) % kStages;
+        constexpr int ST1 = (ST + 1) % kStages, ST2 = (ST + 2) % kStages, ST3 = (ST + 3) % kStages;
         floatx16 (&sc)[2] = sbuf[PAR];
         floatx16 (&sn)[2] = sbuf[PAR ^ 1];
-        const bool fetch = j + 3 < n_vis;
-        if (fetch) fetch_tile(j + 3, ST3);            // stage ST3 held tile j-1: free since the last barrier
-        if (j >= first_mask || (j == nkt - 1 && tail_rows < kBN)) apply_mask(sc, ST, j == nkt - 1 ? tail_rows : kBN);
+        if (j >= first_mask || (j == nkt - 1 && tail_rows < kBN)) apply_mask(sc, ST);
         m_use = (m_ref == -INFINITY) ? 0.f : m_ref;
         psum = 0.f;
-#pragma unroll
-        for (int m = 0; m < kRing; ++m) read_frag(m, ST1, ST);
-        __builtin_amdgcn_sched_barrier(0);
-        // a few probability pairs first: they cover the latency of the first fragment reads
-        prob_pair(sc, 0);
-        prob_pair(sc, 1);
-        prob_pair(sc, 2);
-        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int m = 0; m < 16; ++m) {                // S^T of tile j+1 (after the last tile: stale data, unused)
             const int t = m >> 1, kvb = m & 1;
@@ -373,8 +393,8 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
             } else {
                 sn[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[m % kRing].v, qf[t], sn[kvb], 0, 0, 0);
             }
-            read_frag(m + kRing, ST1, ST);            // the slot is free again
-            if (m < 13) prob_pair(sc, m + 3);
+            read_frag(m + kRing, ST1, ST2, ST);       // the slot is free again
+            prob_pair(sc, m);
             __builtin_amdgcn_sched_barrier(0);
         }
         // offset refresh (rare): first visible key of a row, or a sum that shows the offset fell far behind
@@ -401,30 +421,33 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         }
         lsum += psum;
         __builtin_amdgcn_sched_barrier(0);
+        const bool do_k = j + 4 < n_vis, do_v = j + 3 < n_vis;
 #pragma unroll
         for (int m = 16; m < 32; ++m) {               // O^T += V^T P^T of tile j
             const int kvb = (m - 16) >> 3, t2 = ((m - 16) >> 2) & 1, db = m & 3;
             oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[m % kRing].v, pf[kvb][t2].v, oacc[db], 0, 0, 0);
-            if (m + kRing < 32) read_frag(m + kRing, ST1, ST);
+            read_frag(m + kRing, ST1, ST2, ST);
+            if (m == 19 && do_k) fetch_k(j + 4, ST);
+            if (m == 23 && do_v) fetch_v(j + 3, ST3);
             __builtin_amdgcn_sched_barrier(0);
         }
-        // tile j+2 (fetched during iteration j-1) must have landed before the barrier publishes it; the
-        // transfers of tile j+3 issued above may stay in flight
-        if (fetch) { if (wave == 0 || wave == 7) wait_vm<5>(); else wait_vm<4>(); }
-        else wait_vm<0>();
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier"
+        wait_older_than(do_k, do_v);
+        if (tail_rows < kBN && j + 2 == nkt - 1) seal_tail(ST2);   // its positions landed with V(j+2)
+        asm volatile("s_barrier"
                      :: "v"(sn[0]), "v"(sn[1]), "v"(oacc[0]), "v"(oacc[1]), "v"(oacc[2]), "v"(oacc[3]) : "memory");
     };
 
-    // ---- prologue: tiles 0..2 into LDS, S^T of tile 0
-    if (n_vis > 0) fetch_tile(0, 0);
-    if (n_vis > 1) fetch_tile(1, 1);
-    if (n_vis > 2) fetch_tile(2, 2);
+    // ---- prologue: K(0..3), V(0..2) into LDS, S^T of tile 0, first K fragments of tile 1
+    if (n_vis > 0) { fetch_k(0, 0); fetch_v(0, 0); }
+    if (n_vis > 1) { fetch_k(1, 1); fetch_v(1, 1); }
+    if (n_vis > 2) { fetch_k(2, 2); fetch_v(2, 2); }
+    if (n_vis > 3) fetch_k(3, 3);
     wait_vm<0>();
+    if (tail_rows < kBN && nkt - 1 < 3 && nkt - 1 < n_vis) seal_tail(nkt - 1);
     wg_barrier();
     if (n_vis > 0) {
 #pragma unroll
-        for (int m = 0; m < kRing; ++m) read_frag(m, 0, 0);
+        for (int m = 0; m < kRing; ++m) read_frag(m, 0, 0, 0);
 #pragma unroll
         for (int m = 0; m < 16; ++m) {
             const int t = m >> 1, kvb = m & 1;
@@ -433,8 +456,10 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
                 for (int r = 0; r < 16; ++r) sbuf[0][kvb][r] = 0.f;
             }
             sbuf[0][kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[m % kRing].v, qf[t], sbuf[0][kvb], 0, 0, 0);
-            if (m + kRing < 16) read_frag(m + kRing, 0, 0);
+            if (m + kRing < 16) read_frag(m + kRing, 0, 0, 0);
         }
+#pragma unroll
+        for (int m = 0; m < kRing; ++m) read_frag(m, 1, 1, 0);      // K fragments of tile 1 (stale if absent)
     }
     for (int j = 0; j < n_vis;) {
         iteration(IC<0>{}, IC<0>{}, j); if (++j >= n_vis) break;
