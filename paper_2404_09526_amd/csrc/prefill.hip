@@ -121,11 +121,17 @@ __device__ __forceinline__ void wg_barrier() { asm volatile("s_waitcnt lgkmcnt(0
 template <int V> struct IC { static constexpr int value = V; };
 
 __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_k[kStages][kKTileBytes];
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_v[kStages][kTileBytes];
-    __shared__ __attribute__((aligned(256))) int32_t lds_pos[kStages][kBN];
-    __shared__ int32_t lds_qmm[2][kPfWaves];
-    __shared__ int32_t lds_sched[1 + kPfWaves];   // [0] last visible tile; [1 + w] first tile wavefront w must mask
+    // One LDS block, V stages first: an LDS instruction adds a 16-bit immediate to its address register, so with
+    // each array's base folded into the per-lane register every operand read of the loop needs no address math.
+    constexpr int kLdsV = 0, kLdsK = kLdsV + kStages * kTileBytes, kLdsPos = kLdsK + kStages * kKTileBytes,
+                  kLdsQmm = kLdsPos + kStages * kBN * 4, kLdsSched = kLdsQmm + 2 * kPfWaves * 4,
+                  kLdsTotal = kLdsSched + (1 + kPfWaves) * 4;
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[kLdsTotal];
+    unsigned char (*lds_k)[kKTileBytes] = (unsigned char (*)[kKTileBytes])(smem + kLdsK);
+    unsigned char (*lds_v)[kTileBytes] = (unsigned char (*)[kTileBytes])(smem + kLdsV);
+    int32_t (*lds_pos)[kBN] = (int32_t (*)[kBN])(smem + kLdsPos);
+    int32_t (*lds_qmm)[kPfWaves] = (int32_t (*)[kPfWaves])(smem + kLdsQmm);
+    int32_t* lds_sched = (int32_t*)(smem + kLdsSched);   // [0] last visible tile; [1 + w] first tile wavefront w must mask
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -238,6 +244,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     //      lane L's byte 1024 n + 16 L falls into row B / 272 at B % 272 (a padding slot fetches chunk 0, unused).
     //      Wavefront w issues K transfers w and w + 8; wavefront 7 also the 17th; wavefront 0 the positions.
     const uint32_t kv_row_bytes = (uint32_t)a.Hkv * kHeadDim * 2;
+    const int64_t tile_bytes = (int64_t)kBN * kv_row_bytes;
     const int st_sub = lane >> 4, st_p = lane & 15;
     const int st_r0 = wave * 8 + st_sub, st_r1 = st_r0 + 4;
     auto v_goff = [&](int r_lds, int r_glb) { return r_glb * kv_row_bytes + ((st_p ^ ((r_lds & 3) << 2)) << 4); };
@@ -250,14 +257,13 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     const char* kreq = (const char*)a.k + ((int64_t)kv_lo * a.Hkv + kvh) * (kHeadDim * 2);   // row kv_lo, head kvh
     const char* vreq = (const char*)a.v + ((int64_t)kv_lo * a.Hkv + kvh) * (kHeadDim * 2);
     const int32_t* preq = a.kv_pos + kv_lo;
-    const uint32_t lds_k0 = (uint32_t)(uintptr_t)(ESP_LDS unsigned char*)&lds_k[0][0];
-    const uint32_t lds_v0 = (uint32_t)(uintptr_t)(ESP_LDS unsigned char*)&lds_v[0][0];
-    const uint32_t lds_p0 = (uint32_t)(uintptr_t)(ESP_LDS int32_t*)&lds_pos[0][0];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(ESP_LDS unsigned char*)smem;
+    const uint32_t lds_k0 = lds_base + kLdsK, lds_v0 = lds_base + kLdsV, lds_p0 = lds_base + kLdsPos;
 
     // K of tile t into K stage st: 2 transfers per wavefront, 3 for wavefront 7
     auto fetch_k = [&](int t, int st) {
         t = __builtin_amdgcn_readfirstlane(t);
-        const char* kt = kreq + (int64_t)t * kBN * kv_row_bytes;          // uniform
+        const char* kt = kreq + (int64_t)t * tile_bytes;                   // uniform
         const uint32_t ko = lds_k0 + st * kKTileBytes;
         if (t == nkt - 1 && tail_rows < kBN) {   // rows past the end re-read the last row; their scores get masked
             const int last = tail_rows - 1;
@@ -273,7 +279,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     // V and positions of tile t into V stage st: 2 transfers per wavefront, 3 for wavefront 0
     auto fetch_v = [&](int t, int st) {
         t = __builtin_amdgcn_readfirstlane(t);
-        const char* vt = vreq + (int64_t)t * kBN * kv_row_bytes;
+        const char* vt = vreq + (int64_t)t * tile_bytes;
         const uint32_t vo = lds_v0 + st * kTileBytes + wave * 2048;
         if (t == nkt - 1 && tail_rows < kBN) {
             const int last = tail_rows - 1;
@@ -305,13 +311,13 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
 
     // ---- operand read offsets
     // K (A operand of S^T): row 32*kvb + qi, chunk 2t + hi -> one base per lane, the rest are immediates
-    const uint32_t k_rd = qi * kKRow + hi * 16;
+    const uint32_t k_rd = lds_k0 + qi * kKRow + hi * 16;
     // V (A operand of O^T) by transposing reads: 16 lanes fetch a 4 (kv) x 16 (d) patch
     const int j16 = lane & 15, jq = j16 >> 2, dblk = (lane >> 4) & 1;
     uint32_t v_rd[4];
 #pragma unroll
     for (int db = 0; db < 4; ++db)
-        v_rd[db] = (4 * hi + jq) * 256 + ((((db ^ jq) << 2) + 2 * dblk + ((j16 & 3) >> 1)) << 4) + (j16 & 1) * 8;
+        v_rd[db] = lds_v0 + (4 * hi + jq) * 256 + ((((db ^ jq) << 2) + 2 * dblk + ((j16 & 3) >> 1)) << 4) + (j16 & 1) * 8;
 
     floatx16 oacc[4];
 #pragma unroll
@@ -334,12 +340,12 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     auto read_frag = [&](int m, int st_k, int st_k2, int st_v) {
         if (m < 16 || m >= 32) {
             const int mm = m & 15, t = mm >> 1, kvb = mm & 1;
-            fr[m % kRing].v = *(const bf16x8*)(lds_k[m < 16 ? st_k : st_k2] + kvb * (32 * kKRow) + t * 32 + k_rd);
+            fr[m % kRing].v = *(const ESP_LDS bf16x8*)(uintptr_t)(k_rd + (m < 16 ? st_k : st_k2) * kKTileBytes + kvb * (32 * kKRow) + t * 32);
         } else {
             const int kvb = (m - 16) >> 3, t2 = ((m - 16) >> 2) & 1, db = m & 3;
-            const unsigned char* vp = lds_v[st_v] + (32 * kvb + 16 * t2) * 256 + v_rd[db];
-            fr[m % kRing].s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ESP_LDS short4_t*)(vp));
-            fr[m % kRing].s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ESP_LDS short4_t*)(vp + 8 * 256));
+            const uint32_t vp = v_rd[db] + st_v * kTileBytes + (32 * kvb + 16 * t2) * 256;
+            fr[m % kRing].s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ESP_LDS short4_t*)(uintptr_t)(vp));
+            fr[m % kRing].s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ESP_LDS short4_t*)(uintptr_t)(vp + 8 * 256));
         }
     };
 
@@ -365,7 +371,9 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[kvb][r + 1], a.scale_log2, -m_use));
         psum += p0;
         psum += p1;
-        pf[kvb][(c & 7) >> 2].u[c & 3] = pack_bf16(p0, p1);
+        const uint32_t pk = pack_bf16(p0, p1);
+        asm volatile("" :: "v"(pk));   // pack here, among the MFMAs of S^T, not in a bunch in front of the PV product
+        pf[kvb][(c & 7) >> 2].u[c & 3] = pk;
     };
 
     // One tile.  On entry: scores of tile j in sbuf[PAR], the first kRing K fragments of tile j+1 in fr.
