@@ -260,12 +260,11 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     const uint32_t lds_base = (uint32_t)(uintptr_t)(ESP_LDS unsigned char*)smem;
     const uint32_t lds_k0 = lds_base + kLdsK, lds_v0 = lds_base + kLdsV, lds_p0 = lds_base + kLdsPos;
 
-    // K of tile t into K stage st: 2 transfers per wavefront, 3 for wavefront 7
-    auto fetch_k = [&](int t, int st) {
-        t = __builtin_amdgcn_readfirstlane(t);
-        const char* kt = kreq + (int64_t)t * tile_bytes;                   // uniform
+    // K tile at kt into K stage st: 2 transfers per wavefront, 3 for wavefront 7.  `tail`: it is the ragged last
+    // tile, whose rows past the end re-read the last row (their scores get masked).
+    auto fetch_k = [&](const char* kt, int st, bool tail) {
         const uint32_t ko = lds_k0 + st * kKTileBytes;
-        if (t == nkt - 1 && tail_rows < kBN) {   // rows past the end re-read the last row; their scores get masked
+        if (__builtin_expect(tail, 0)) {
             const int last = tail_rows - 1;
             load_to_lds_b128(ko + 1024 * wave, kt, k_goff(wave, last));
             load_to_lds_b128(ko + 1024 * (wave + 8), kt, k_goff(wave + 8, last));
@@ -276,33 +275,21 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
             if (wave == 7) load_to_lds_b128(ko + 1024 * 16, kt, gk2);
         }
     };
-    // V and positions of tile t into V stage st: 2 transfers per wavefront, 3 for wavefront 0
-    auto fetch_v = [&](int t, int st) {
-        t = __builtin_amdgcn_readfirstlane(t);
-        const char* vt = vreq + (int64_t)t * tile_bytes;
+    // V tile at vt and its positions at pt into V stage st: 2 transfers per wavefront, 3 for wavefront 0
+    auto fetch_v = [&](const char* vt, const int32_t* pt, int st, bool tail) {
         const uint32_t vo = lds_v0 + st * kTileBytes + wave * 2048;
-        if (t == nkt - 1 && tail_rows < kBN) {
+        if (__builtin_expect(tail, 0)) {
             const int last = tail_rows - 1;
             load_to_lds_b128(vo, vt, v_goff(st_r0, min(st_r0, last)));
             load_to_lds_b128(vo + 1024, vt, v_goff(st_r1, min(st_r1, last)));
-            if (wave == 0) load_to_lds_b32(lds_p0 + st * (kBN * 4), preq + t * kBN, min(lane, last) * 4);
+            if (wave == 0) load_to_lds_b32(lds_p0 + st * (kBN * 4), pt, min(lane, last) * 4);
         } else {
             load_to_lds_b128(vo, vt, gv0);
             load_to_lds_b128(vo + 1024, vt, gv1);
-            if (wave == 0) load_to_lds_b32(lds_p0 + st * (kBN * 4), preq + t * kBN, lane * 4);
+            if (wave == 0) load_to_lds_b32(lds_p0 + st * (kBN * 4), pt, lane * 4);
         }
     };
-    // transfers in flight that may stay in flight at the end of an iteration: the ones it issued itself
-    auto wait_older_than = [&](bool did_k, bool did_v) {
-        const int n = (did_k ? 2 + (wave == 7) : 0) + (did_v ? 2 + (wave == 0) : 0);
-        switch (n) {
-            case 5: wait_vm<5>(); break;
-            case 4: wait_vm<4>(); break;
-            case 3: wait_vm<3>(); break;
-            case 2: wait_vm<2>(); break;
-            default: wait_vm<0>(); break;
-        }
-    };
+    const bool extra_transfer = wave == 0 || wave == 7;
     // positions past the end of a ragged last tile become INT_MAX, hidden from every query
     auto seal_tail = [&](int st) {
         if (wave == 0 && lane >= tail_rows) lds_pos[st][lane] = INT_MAX;
@@ -364,7 +351,8 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     };
 
     float psum, m_use;
-    // probabilities of score pair c (0..15) of the current tile: exp2, partial sum, bf16 pack
+    // probabilities of score pair c (0..15) of the current tile: exp2, fp32 partial sum (of the unrounded
+    // values: the log-sum-exp has to be good to 1e-4), bf16 pack
     auto prob_pair = [&](const floatx16 (&sc)[2], int c) {
         const int kvb = c >> 3, r = 2 * (c & 7);
         const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[kvb][r], a.scale_log2, -m_use));
@@ -375,6 +363,12 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         asm volatile("" :: "v"(pk));   // pack here, among the MFMAs of S^T, not in a bunch in front of the PV product
         pf[kvb][(c & 7) >> 2].u[c & 3] = pk;
     };
+
+    const int ragged_tile = tail_rows < kBN ? nkt - 1 : -8;          // index of the ragged last tile, if any
+    const int mask_from = min(first_mask, tail_rows < kBN ? nkt - 1 : nkt);   // first tile this wavefront masks
+    const char* k_next = kreq + 4 * tile_bytes;                       // K tile that iteration 0 fetches
+    const char* v_next = vreq + 3 * tile_bytes;                       // V tile that iteration 0 fetches
+    const int32_t* p_next = preq + 3 * kBN;
 
     // One tile.  On entry: scores of tile j in sbuf[PAR], the first kRing K fragments of tile j+1 in fr.
     // The exp2 work of tile j is interleaved with S^T of tile j+1 (into sbuf[PAR^1]); then O^T += V^T P^T of
@@ -387,7 +381,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         constexpr int ST1 = (ST + 1) % kStages, ST2 = (ST + 2) % kStages, ST3 = (ST + 3) % kStages;
         floatx16 (&sc)[2] = sbuf[PAR];
         floatx16 (&sn)[2] = sbuf[PAR ^ 1];
-        if (j >= first_mask || (j == nkt - 1 && tail_rows < kBN)) apply_mask(sc, ST);
+        if (j >= mask_from) apply_mask(sc, ST);
         m_use = (m_ref == -INFINITY) ? 0.f : m_ref;
         psum = 0.f;
 #pragma unroll
@@ -429,29 +423,32 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         }
         lsum += psum;
         __builtin_amdgcn_sched_barrier(0);
-        const bool do_k = j + 4 < n_vis, do_v = j + 3 < n_vis;
+        const bool do_k = j < n_vis - 4, do_v = j < n_vis - 3;
 #pragma unroll
         for (int m = 16; m < 32; ++m) {               // O^T += V^T P^T of tile j
             const int kvb = (m - 16) >> 3, t2 = ((m - 16) >> 2) & 1, db = m & 3;
             oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[m % kRing].v, pf[kvb][t2].v, oacc[db], 0, 0, 0);
             read_frag(m + kRing, ST1, ST2, ST);
-            if (m == 19 && do_k) fetch_k(j + 4, ST);
-            if (m == 23 && do_v) fetch_v(j + 3, ST3);
+            if (m == 19 && do_k) fetch_k(k_next, ST, j + 4 == ragged_tile);
+            if (m == 23 && do_v) fetch_v(v_next, p_next, ST3, j + 3 == ragged_tile);
             __builtin_amdgcn_sched_barrier(0);
         }
-        wait_older_than(do_k, do_v);
-        if (tail_rows < kBN && j + 2 == nkt - 1) seal_tail(ST2);   // its positions landed with V(j+2)
+        k_next += tile_bytes; v_next += tile_bytes; p_next += kBN;
+        // what iteration j-1 fetched must have landed; this iteration's own transfers may stay in flight
+        if (do_k) { if (extra_transfer) wait_vm<5>(); else wait_vm<4>(); }
+        else wait_vm<0>();
+        if (__builtin_expect(j + 2 == ragged_tile, 0)) seal_tail(ST2);   // its positions landed with V(j+2)
         asm volatile("s_barrier"
                      :: "v"(sn[0]), "v"(sn[1]), "v"(oacc[0]), "v"(oacc[1]), "v"(oacc[2]), "v"(oacc[3]) : "memory");
     };
 
     // ---- prologue: K(0..3), V(0..2) into LDS, S^T of tile 0, first K fragments of tile 1
-    if (n_vis > 0) { fetch_k(0, 0); fetch_v(0, 0); }
-    if (n_vis > 1) { fetch_k(1, 1); fetch_v(1, 1); }
-    if (n_vis > 2) { fetch_k(2, 2); fetch_v(2, 2); }
-    if (n_vis > 3) fetch_k(3, 3);
+    if (n_vis > 0) { fetch_k(kreq, 0, 0 == ragged_tile); fetch_v(vreq, preq, 0, 0 == ragged_tile); }
+    if (n_vis > 1) { fetch_k(kreq + tile_bytes, 1, 1 == ragged_tile); fetch_v(vreq + tile_bytes, preq + kBN, 1, 1 == ragged_tile); }
+    if (n_vis > 2) { fetch_k(kreq + 2 * tile_bytes, 2, 2 == ragged_tile); fetch_v(vreq + 2 * tile_bytes, preq + 2 * kBN, 2, 2 == ragged_tile); }
+    if (n_vis > 3) fetch_k(kreq + 3 * tile_bytes, 3, 3 == ragged_tile);
     wait_vm<0>();
-    if (tail_rows < kBN && nkt - 1 < 3 && nkt - 1 < n_vis) seal_tail(nkt - 1);
+    if (ragged_tile >= 0 && ragged_tile < 3 && ragged_tile < n_vis) seal_tail(ragged_tile);
     wg_barrier();
     if (n_vis > 0) {
 #pragma unroll
