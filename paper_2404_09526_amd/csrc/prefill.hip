@@ -370,12 +370,16 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     const char* v_next = vreq + 3 * tile_bytes;                       // V tile that iteration 0 fetches
     const int32_t* p_next = preq + 3 * kBN;
 
-    // One tile.  On entry: scores of tile j in sbuf[PAR], the first kRing K fragments of tile j+1 in fr.
+    // One tile, in two halves separated by workgroup barriers; wavefronts 4-7 run half an iteration behind
+    // wavefronts 0-3 (one extra barrier before their loop, one after the loop of the others).
+    // On entry: scores of tile j in sbuf[PAR], the first kRing K fragments of tile j+1 in fr.
     // The exp2 work of tile j is interleaved with S^T of tile j+1 (into sbuf[PAR^1]); then O^T += V^T P^T of
     // tile j, with the fetch of K(j+4), V(j+3) and the first K fragments of tile j+2 issued among its MFMAs.
     // LDS stages: K(t), V(t) and the positions of tile t live in stage t % 4.  K(j) is dead during iteration j
     // (S^T of tile j was finished before the previous barrier), so K(j+4) may overwrite it; V(j+3) overwrites
-    // V(j-1).  What iteration j-1 fetched has landed before the barrier that ends iteration j.
+    // V(j-1); both were last read at least one barrier earlier by either group.  What a wavefront fetched in its
+    // iteration j-1 has landed before the barrier that ends its iteration j; the first reads of those tiles come
+    // at least one further barrier later, by which time the other group has passed the same point.
     auto iteration = [&](auto st_c, auto par_c, int j) {
         constexpr int ST = decltype(st_c)::value, PAR = decltype(par_c)::value;
         constexpr int ST1 = (ST + 1) % kStages, ST2 = (ST + 2) % kStages, ST3 = (ST + 3) % kStages;
@@ -423,6 +427,9 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         }
         lsum += psum;
         __builtin_amdgcn_sched_barrier(0);
+        // half-iteration boundary: the other wavefront of this SIMD is half an iteration away, so that the
+        // vector-heavy half of one runs beside the MFMA-only half of the other
+        asm volatile("s_barrier" :: "v"(sn[0]), "v"(sn[1]), "v"(pf[0][0].v), "v"(pf[0][1].v), "v"(pf[1][0].v), "v"(pf[1][1].v), "v"(lsum) : "memory");
         const bool do_k = j < n_vis - 4, do_v = j < n_vis - 3;
 #pragma unroll
         for (int m = 16; m < 32; ++m) {               // O^T += V^T P^T of tile j
@@ -466,12 +473,15 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
         for (int m = 0; m < kRing; ++m) read_frag(m, 1, 1, 0);      // K fragments of tile 1 (stale if absent)
     }
+    const bool group_b = wave >= kPfWaves / 2;     // wavefronts w and w + 4 share a SIMD
+    if (group_b) asm volatile("s_barrier" ::: "memory");
     for (int j = 0; j < n_vis;) {
         iteration(IC<0>{}, IC<0>{}, j); if (++j >= n_vis) break;
         iteration(IC<1>{}, IC<1>{}, j); if (++j >= n_vis) break;
         iteration(IC<2>{}, IC<0>{}, j); if (++j >= n_vis) break;
         iteration(IC<3>{}, IC<1>{}, j); ++j;
     }
+    if (!group_b) asm volatile("s_barrier" ::: "memory");
 
     // ---- epilogue: normalise, write O (bf16) and LSE (natural log)
     const float ltot = half_swap_sum(lsum);
