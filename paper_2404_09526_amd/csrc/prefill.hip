@@ -125,13 +125,12 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     // each array's base folded into the per-lane register every operand read of the loop needs no address math.
     constexpr int kLdsV = 0, kLdsK = kLdsV + kStages * kTileBytes, kLdsPos = kLdsK + kStages * kKTileBytes,
                   kLdsQmm = kLdsPos + kStages * kBN * 4, kLdsSched = kLdsQmm + 2 * kPfWaves * 4,
-                  kLdsTotal = kLdsSched + (1 + kPfWaves) * 4;
+                  kLdsTotal = kLdsSched + kPfWaves * (1 + kPfWaves) * 4;
     __shared__ __attribute__((aligned(1024))) unsigned char smem[kLdsTotal];
     unsigned char (*lds_k)[kKTileBytes] = (unsigned char (*)[kKTileBytes])(smem + kLdsK);
     unsigned char (*lds_v)[kTileBytes] = (unsigned char (*)[kTileBytes])(smem + kLdsV);
     int32_t (*lds_pos)[kBN] = (int32_t (*)[kBN])(smem + kLdsPos);
     int32_t (*lds_qmm)[kPfWaves] = (int32_t (*)[kPfWaves])(smem + kLdsQmm);
-    int32_t* lds_sched = (int32_t*)(smem + kLdsSched);   // [0] last visible tile; [1 + w] first tile wavefront w must mask
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -205,8 +204,6 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     wave_qmin = __builtin_amdgcn_readfirstlane(wave_qmin);
     wave_qmax = __builtin_amdgcn_readfirstlane(wave_qmax);
     if (lane == 0) { lds_qmm[0][wave] = wave_qmin; lds_qmm[1][wave] = wave_qmax; }
-    if (tid == 0) lds_sched[0] = -1;
-    if (tid < kPfWaves) lds_sched[1 + tid] = nkt;
     __syncthreads();
 
     // ---- tile schedule of this workgroup: n_vis = 1 + last tile some row can see (tiles before it that are
@@ -218,23 +215,42 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         int wg_qmax = lds_qmm[1][0];
 #pragma unroll
         for (int w = 1; w < kPfWaves; ++w) wg_qmax = max(wg_qmax, lds_qmm[1][w]);
+        int qmin_w[kPfWaves];
+#pragma unroll
+        for (int w = 0; w < kPfWaves; ++w) qmin_w[w] = lds_qmm[0][w];
+        // every thread looks at tiles tid, tid + 512, ...; wavefront-wide ballots turn the per-tile tests into bit
+        // masks, whose highest / lowest set bit gives this wavefront's candidates (no atomics on shared words)
         int last_vis = -1, fm[kPfWaves];
 #pragma unroll
         for (int w = 0; w < kPfWaves; ++w) fm[w] = nkt;
-        for (int t = tid; t < nkt; t += kPfWaves * 64) {
-            const int2 mm = a.tile_mm[tile0 + t];
-            if (mm.x <= wg_qmax) last_vis = max(last_vis, t);
+        for (int t0 = wave * 64; t0 < nkt; t0 += kPfWaves * 64) {
+            const int t = t0 + lane;
+            int2 mm = make_int2(INT_MAX, INT_MIN);                  // beyond the end: hidden, needs no mask
+            if (t < nkt) mm = a.tile_mm[tile0 + t];
+            const uint64_t vis = __builtin_amdgcn_ballot_w64(mm.x <= wg_qmax);
+            if (vis) last_vis = t0 + 63 - __builtin_clzll(vis);
 #pragma unroll
-            for (int w = 0; w < kPfWaves; ++w)
-                if (mm.y > lds_qmm[0][w]) fm[w] = min(fm[w], t);
+            for (int w = 0; w < kPfWaves; ++w) {
+                const uint64_t mk = __builtin_amdgcn_ballot_w64(mm.y > qmin_w[w]);
+                if (mk && fm[w] == nkt) fm[w] = t0 + __builtin_ctzll(mk);
+            }
         }
-        if (last_vis >= 0) atomicMax(&lds_sched[0], last_vis);
+        // candidates of wavefront `wave` -> LDS (one row per scanning wavefront), then everyone combines the rows
+        int32_t (*cand)[1 + kPfWaves] = (int32_t (*)[1 + kPfWaves])(smem + kLdsSched);
+        if (lane == 0) {
+            cand[wave][0] = last_vis;
 #pragma unroll
-        for (int w = 0; w < kPfWaves; ++w)
-            if (fm[w] < nkt) atomicMin(&lds_sched[1 + w], fm[w]);
+            for (int w = 0; w < kPfWaves; ++w) cand[wave][1 + w] = fm[w];
+        }
         __syncthreads();
-        n_vis = __builtin_amdgcn_readfirstlane(lds_sched[0]) + 1;
-        first_mask = __builtin_amdgcn_readfirstlane(lds_sched[1 + wave]);
+        int lv = -1, fmk = nkt;
+#pragma unroll
+        for (int sw = 0; sw < kPfWaves; ++sw) {
+            lv = max(lv, cand[sw][0]);
+            fmk = min(fmk, cand[sw][1 + wave]);
+        }
+        n_vis = __builtin_amdgcn_readfirstlane(lv) + 1;
+        first_mask = __builtin_amdgcn_readfirstlane(fmk);
     }
 
     // ---- global -> LDS in transfers of 64 lanes x 16 bytes = 1 KiB of consecutive LDS bytes.
