@@ -182,6 +182,73 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     const int nkt = (kv_len + kBN - 1) / kBN;
     const int tail_rows = kv_len - (nkt - 1) * kBN;    // rows of the last tile (64 when not ragged)
 
+    // ---- global -> LDS in transfers of 64 lanes x 16 bytes = 1 KiB of consecutive LDS bytes.
+    //      V tile (rows of 256 B, chunks XOR-swizzled): wavefront w moves rows 8w .. 8w+7 in two transfers; lane L
+    //      writes LDS chunk L % 16 of row r = base + L / 16, so it fetches the global chunk (L % 16) ^ f(r).
+    //      K tile (rows padded to 272 B): transfer n covers LDS bytes [1024 n, 1024 n + 1024) of the padded tile;
+    //      lane L's byte 1024 n + 16 L falls into row B / 272 at B % 272 (a padding slot fetches chunk 0, unused).
+    //      Wavefront w issues K transfers w and w + 8; wavefront 7 also the 17th; wavefront 0 the positions.
+    const uint32_t kv_row_bytes = (uint32_t)a.Hkv * kHeadDim * 2;
+    const int64_t tile_bytes = (int64_t)kBN * kv_row_bytes;
+    const int st_sub = lane >> 4, st_p = lane & 15;
+    const int st_r0 = wave * 8 + st_sub, st_r1 = st_r0 + 4;
+    auto v_goff = [&](int r_lds, int r_glb) { return r_glb * kv_row_bytes + ((st_p ^ ((r_lds & 3) << 2)) << 4); };
+    auto k_goff = [&](int n, int last_row) {
+        const int B = 1024 * n + 16 * lane, row = B / kKRow, within = B - row * kKRow;
+        return (uint32_t)(min(row, last_row) * kv_row_bytes + (within < 256 ? within : 0));
+    };
+    const uint32_t gv0 = v_goff(st_r0, st_r0), gv1 = v_goff(st_r1, st_r1);
+    const uint32_t gk0 = k_goff(wave, kBN - 1), gk1 = k_goff(wave + 8, kBN - 1), gk2 = k_goff(16, kBN - 1);
+    const char* kreq = (const char*)a.k + ((int64_t)kv_lo * a.Hkv + kvh) * (kHeadDim * 2);   // row kv_lo, head kvh
+    const char* vreq = (const char*)a.v + ((int64_t)kv_lo * a.Hkv + kvh) * (kHeadDim * 2);
+    const int32_t* preq = a.kv_pos + kv_lo;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(ESP_LDS unsigned char*)smem;
+    const uint32_t lds_k0 = lds_base + kLdsK, lds_v0 = lds_base + kLdsV, lds_p0 = lds_base + kLdsPos;
+
+    // K tile at kt into K stage st: 2 transfers per wavefront, 3 for wavefront 7.  `tail`: it is the ragged last
+    // tile, whose rows past the end re-read the last row (their scores get masked).
+    auto fetch_k = [&](const char* kt, int st, bool tail) {
+        const uint32_t ko = lds_k0 + st * kKTileBytes;
+        if (__builtin_expect(tail, 0)) {
+            const int last = tail_rows - 1;
+            load_to_lds_b128(ko + 1024 * wave, kt, k_goff(wave, last));
+            load_to_lds_b128(ko + 1024 * (wave + 8), kt, k_goff(wave + 8, last));
+            if (wave == 7) load_to_lds_b128(ko + 1024 * 16, kt, k_goff(16, last));
+        } else {
+            load_to_lds_b128(ko + 1024 * wave, kt, gk0);
+            load_to_lds_b128(ko + 1024 * (wave + 8), kt, gk1);
+            if (wave == 7) load_to_lds_b128(ko + 1024 * 16, kt, gk2);
+        }
+    };
+    // V tile at vt and its positions at pt into V stage st: 2 transfers per wavefront, 3 for wavefront 0
+    auto fetch_v = [&](const char* vt, const int32_t* pt, int st, bool tail) {
+        const uint32_t vo = lds_v0 + st * kTileBytes + wave * 2048;
+        if (__builtin_expect(tail, 0)) {
+            const int last = tail_rows - 1;
+            load_to_lds_b128(vo, vt, v_goff(st_r0, min(st_r0, last)));
+            load_to_lds_b128(vo + 1024, vt, v_goff(st_r1, min(st_r1, last)));
+            if (wave == 0) load_to_lds_b32(lds_p0 + st * (kBN * 4), pt, min(lane, last) * 4);
+        } else {
+            load_to_lds_b128(vo, vt, gv0);
+            load_to_lds_b128(vo + 1024, vt, gv1);
+            if (wave == 0) load_to_lds_b32(lds_p0 + st * (kBN * 4), pt, lane * 4);
+        }
+    };
+    const bool extra_transfer = wave == 0 || wave == 7;
+    // positions past the end of a ragged last tile become INT_MAX, hidden from every query
+    auto seal_tail = [&](int st) {
+        if (wave == 0 && lane >= tail_rows) lds_pos[st][lane] = INT_MAX;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // written before the barrier that follows
+    };
+
+    // the first tiles are requested right away, so that their latency hides behind the Q load and the schedule
+    // scan (tiles the scan later finds hidden are fetched for nothing, which is harmless: they exist)
+    const int ragged_tile = tail_rows < kBN ? nkt - 1 : -8;          // index of the ragged last tile, if any
+    if (nkt > 0) { fetch_k(kreq, 0, 0 == ragged_tile); fetch_v(vreq, preq, 0, 0 == ragged_tile); }
+    if (nkt > 1) { fetch_k(kreq + tile_bytes, 1, 1 == ragged_tile); fetch_v(vreq + tile_bytes, preq + kBN, 1, 1 == ragged_tile); }
+    if (nkt > 2) { fetch_k(kreq + 2 * tile_bytes, 2, 2 == ragged_tile); fetch_v(vreq + 2 * tile_bytes, preq + 2 * kBN, 2, 2 == ragged_tile); }
+    if (nkt > 3) fetch_k(kreq + 3 * tile_bytes, 3, 3 == ragged_tile);
+
     // ---- this lane's query row (column of S^T) and its Q fragment
     const int qi = lane & 31, hi = lane >> 5;
     const int my_row = q_lo + wave * 32 + qi;
@@ -253,65 +320,6 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         first_mask = __builtin_amdgcn_readfirstlane(fmk);
     }
 
-    // ---- global -> LDS in transfers of 64 lanes x 16 bytes = 1 KiB of consecutive LDS bytes.
-    //      V tile (rows of 256 B, chunks XOR-swizzled): wavefront w moves rows 8w .. 8w+7 in two transfers; lane L
-    //      writes LDS chunk L % 16 of row r = base + L / 16, so it fetches the global chunk (L % 16) ^ f(r).
-    //      K tile (rows padded to 272 B): transfer n covers LDS bytes [1024 n, 1024 n + 1024) of the padded tile;
-    //      lane L's byte 1024 n + 16 L falls into row B / 272 at B % 272 (a padding slot fetches chunk 0, unused).
-    //      Wavefront w issues K transfers w and w + 8; wavefront 7 also the 17th; wavefront 0 the positions.
-    const uint32_t kv_row_bytes = (uint32_t)a.Hkv * kHeadDim * 2;
-    const int64_t tile_bytes = (int64_t)kBN * kv_row_bytes;
-    const int st_sub = lane >> 4, st_p = lane & 15;
-    const int st_r0 = wave * 8 + st_sub, st_r1 = st_r0 + 4;
-    auto v_goff = [&](int r_lds, int r_glb) { return r_glb * kv_row_bytes + ((st_p ^ ((r_lds & 3) << 2)) << 4); };
-    auto k_goff = [&](int n, int last_row) {
-        const int B = 1024 * n + 16 * lane, row = B / kKRow, within = B - row * kKRow;
-        return (uint32_t)(min(row, last_row) * kv_row_bytes + (within < 256 ? within : 0));
-    };
-    const uint32_t gv0 = v_goff(st_r0, st_r0), gv1 = v_goff(st_r1, st_r1);
-    const uint32_t gk0 = k_goff(wave, kBN - 1), gk1 = k_goff(wave + 8, kBN - 1), gk2 = k_goff(16, kBN - 1);
-    const char* kreq = (const char*)a.k + ((int64_t)kv_lo * a.Hkv + kvh) * (kHeadDim * 2);   // row kv_lo, head kvh
-    const char* vreq = (const char*)a.v + ((int64_t)kv_lo * a.Hkv + kvh) * (kHeadDim * 2);
-    const int32_t* preq = a.kv_pos + kv_lo;
-    const uint32_t lds_base = (uint32_t)(uintptr_t)(ESP_LDS unsigned char*)smem;
-    const uint32_t lds_k0 = lds_base + kLdsK, lds_v0 = lds_base + kLdsV, lds_p0 = lds_base + kLdsPos;
-
-    // K tile at kt into K stage st: 2 transfers per wavefront, 3 for wavefront 7.  `tail`: it is the ragged last
-    // tile, whose rows past the end re-read the last row (their scores get masked).
-    auto fetch_k = [&](const char* kt, int st, bool tail) {
-        const uint32_t ko = lds_k0 + st * kKTileBytes;
-        if (__builtin_expect(tail, 0)) {
-            const int last = tail_rows - 1;
-            load_to_lds_b128(ko + 1024 * wave, kt, k_goff(wave, last));
-            load_to_lds_b128(ko + 1024 * (wave + 8), kt, k_goff(wave + 8, last));
-            if (wave == 7) load_to_lds_b128(ko + 1024 * 16, kt, k_goff(16, last));
-        } else {
-            load_to_lds_b128(ko + 1024 * wave, kt, gk0);
-            load_to_lds_b128(ko + 1024 * (wave + 8), kt, gk1);
-            if (wave == 7) load_to_lds_b128(ko + 1024 * 16, kt, gk2);
-        }
-    };
-    // V tile at vt and its positions at pt into V stage st: 2 transfers per wavefront, 3 for wavefront 0
-    auto fetch_v = [&](const char* vt, const int32_t* pt, int st, bool tail) {
-        const uint32_t vo = lds_v0 + st * kTileBytes + wave * 2048;
-        if (__builtin_expect(tail, 0)) {
-            const int last = tail_rows - 1;
-            load_to_lds_b128(vo, vt, v_goff(st_r0, min(st_r0, last)));
-            load_to_lds_b128(vo + 1024, vt, v_goff(st_r1, min(st_r1, last)));
-            if (wave == 0) load_to_lds_b32(lds_p0 + st * (kBN * 4), pt, min(lane, last) * 4);
-        } else {
-            load_to_lds_b128(vo, vt, gv0);
-            load_to_lds_b128(vo + 1024, vt, gv1);
-            if (wave == 0) load_to_lds_b32(lds_p0 + st * (kBN * 4), pt, lane * 4);
-        }
-    };
-    const bool extra_transfer = wave == 0 || wave == 7;
-    // positions past the end of a ragged last tile become INT_MAX, hidden from every query
-    auto seal_tail = [&](int st) {
-        if (wave == 0 && lane >= tail_rows) lds_pos[st][lane] = INT_MAX;
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // written before the barrier that follows
-    };
-
     // ---- operand read offsets
     // K (A operand of S^T): row 32*kvb + qi, chunk 2t + hi -> one base per lane, the rest are immediates
     const uint32_t k_rd = lds_k0 + qi * kKRow + hi * 16;
@@ -380,7 +388,6 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         pf[kvb][(c & 7) >> 2].u[c & 3] = pk;
     };
 
-    const int ragged_tile = tail_rows < kBN ? nkt - 1 : -8;          // index of the ragged last tile, if any
     const int mask_from = min(first_mask, tail_rows < kBN ? nkt - 1 : nkt);   // first tile this wavefront masks
     const char* k_next = kreq + 4 * tile_bytes;                       // K tile that iteration 0 fetches
     const char* v_next = vreq + 3 * tile_bytes;                       // V tile that iteration 0 fetches
@@ -465,13 +472,9 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
                      :: "v"(sn[0]), "v"(sn[1]), "v"(oacc[0]), "v"(oacc[1]), "v"(oacc[2]), "v"(oacc[3]) : "memory");
     };
 
-    // ---- prologue: K(0..3), V(0..2) into LDS, S^T of tile 0, first K fragments of tile 1
-    if (n_vis > 0) { fetch_k(kreq, 0, 0 == ragged_tile); fetch_v(vreq, preq, 0, 0 == ragged_tile); }
-    if (n_vis > 1) { fetch_k(kreq + tile_bytes, 1, 1 == ragged_tile); fetch_v(vreq + tile_bytes, preq + kBN, 1, 1 == ragged_tile); }
-    if (n_vis > 2) { fetch_k(kreq + 2 * tile_bytes, 2, 2 == ragged_tile); fetch_v(vreq + 2 * tile_bytes, preq + 2 * kBN, 2, 2 == ragged_tile); }
-    if (n_vis > 3) fetch_k(kreq + 3 * tile_bytes, 3, 3 == ragged_tile);
+    // ---- prologue: K(0..3), V(0..2) were requested at kernel entry; S^T of tile 0, first K fragments of tile 1
     wait_vm<0>();
-    if (ragged_tile >= 0 && ragged_tile < 3 && ragged_tile < n_vis) seal_tail(ragged_tile);
+    if (ragged_tile >= 0 && ragged_tile < 3) seal_tail(ragged_tile);
     wg_barrier();
     if (n_vis > 0) {
 #pragma unroll
