@@ -33,7 +33,11 @@ def parse():
     ap.add_argument("--workload", default="lwm7b", choices=["lwm7b", "long", "mixed"],
                     help="lwm7b = configs[1]+configs[2] (default, the bench line); long = configs[3]; mixed = configs[4]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--traffic-json", default=None, help="JSON file with measured HBM bytes per launch (from rocprofv3 --pmc)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 1 GiB device-to-device copy kernel (known traffic, to scale rocprofv3 --pmc byte counters)")
+    ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "bench_lwm7b_hbm_traffic.json"),
+                    help="JSON with HBM bytes per launch measured by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this workload "
+                         "(see profiles/bench_lwm7b_hbm_traffic.md); used for roofline.traffic of the default workload")
     return ap.parse_args()
 
 
@@ -166,6 +170,12 @@ def main():
         if rec is not None:
             rec.append(e)
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # 1 GiB read + 1 GiB written by one elementwise kernel
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -208,7 +218,7 @@ def main():
                                      "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "traffic": None, "launch_ms": ms_decode,
                                      "bytes_per_launch": byts}
         result["config"].update({"decode_B": dc.B, "decode_total_tokens": dc.total_tokens, "pool_slots": dc.num_slots})
-    if args.traffic_json and os.path.exists(args.traffic_json):
+    if args.workload == "lwm7b" and args.traffic_json and os.path.exists(args.traffic_json):
         tr = json.load(open(args.traffic_json))
         result["roofline"]["traffic"] = tr.get("prefill_kernel")
         if "roofline_decode" in result:
