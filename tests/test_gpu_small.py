@@ -240,3 +240,44 @@ def test_request_without_keys_in_this_shard(esp, cuda):
     Or, Lr = oracle.partial_attn(wl.bits(pc.q), wl.bits(k), wl.bits(v), wl.host_i32(pc.q_pos), wl.host_i32(kv_pos), pc.scale,
                                  True, rows, heads)
     check_o_lse(O[100:].float().cpu().numpy().reshape(-1, 128), LSE[100:].cpu().numpy().reshape(-1), Or, Lr, "nokeys")
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(32, 4), (64, 64)])
+def test_decode_wide_groups_and_many_head_blocks(esp, cuda, Hq, Hkv):
+    """G = 8 query heads per KV head; 64 KV heads = 16 one-KiB head blocks (two workgroups along y)."""
+    dc = wl.decode_pool(f"decode-{Hq}/{Hkv}", [17, 0, 2049, 300], 4096, Hq, Hkv, 33, cuda, n_new=0)
+    run_decode_case(esp, dc)
+
+
+def test_prefill_shard_entirely_in_the_future(esp, cuda):
+    """No tile of the shard is visible to any row: nothing is swept, O = 0 and LSE = -inf everywhere."""
+    pc = wl.contiguous_prefill("future", 300, 0, [(5000, 5500)], 4, 4, 26, cuda)
+    s = pc.shards[0]
+    say("future shard")
+    O, LSE = esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos, softmax_scale=pc.scale)
+    torch.cuda.synchronize()
+    assert torch.isneginf(LSE).all() and (O == 0).all()
+
+
+def test_prefill_empty_shard_and_large_positions(esp, cuda):
+    """Tkv = 0 (an instance that holds nothing of this request) and positions near the top of the int32 range."""
+    pc = wl.contiguous_prefill("big-positions", 70, 2**31 - 400, [(2**31 - 600, 2**31 - 300)], 4, 4, 27, cuda)
+    run_prefill_case(esp, pc)
+    empty_k = torch.empty((0, 4, 128), dtype=torch.bfloat16, device=cuda)
+    empty_p = torch.empty((0,), dtype=torch.int32, device=cuda)
+    O, LSE = esp.esp_partial_attn_prefill(pc.q, empty_k, empty_k, pc.q_pos, empty_p, softmax_scale=pc.scale)
+    torch.cuda.synchronize()
+    assert torch.isneginf(LSE).all() and (O == 0).all()
+
+
+def test_prefill_large_scores_refresh_the_softmax_offset(esp, cuda):
+    """Scores far above the first tile's (a late 'attention sink') and far below it: the optimistic offset has to
+    be refreshed by the sum check, and tiny probabilities must not be lost."""
+    pc = wl.contiguous_prefill("sink", 64, 1000, [(0, 640)], 4, 4, 28, cuda, causal=False)
+    s = pc.shards[0]
+    s.k[300:303] *= 40.0          # a few keys with very large scores in tile 4
+    s.k[0:64] *= 0.01
+    run_prefill_case(esp, pc)
+    pc2 = wl.contiguous_prefill("sink-first", 64, 1000, [(0, 640)], 4, 4, 29, cuda, causal=False)
+    pc2.shards[0].k[3:5] *= 60.0  # the huge scores come first, everything later is ~2^-80 of them
+    run_prefill_case(esp, pc2)
