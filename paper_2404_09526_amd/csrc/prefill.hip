@@ -241,6 +241,14 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // written before the barrier that follows
     };
 
+    // ---- this lane's query row (column of S^T); its position is needed first (schedule scan), so it is loaded first
+    const int qi = lane & 31, hi = lane >> 5;
+    const int my_row = q_lo + wave * 32 + qi;
+    const bool row_ok = my_row < q_hi;
+    const int ld_row = row_ok ? my_row : q_hi - 1;
+    // effective query position: non-causal rows see every real key
+    const int my_qpos = a.causal ? a.q_pos[ld_row] : INT_MAX - 1;   // INT_MAX marks rows past a ragged tail
+
     // the first tiles are requested right away, so that their latency hides behind the Q load and the schedule
     // scan (tiles the scan later finds hidden are fetched for nothing, which is harmless: they exist)
     const int ragged_tile = tail_rows < kBN ? nkt - 1 : -8;          // index of the ragged last tile, if any
@@ -249,19 +257,13 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     if (nkt > 2) { fetch_k(kreq + 2 * tile_bytes, 2, 2 == ragged_tile); fetch_v(vreq + 2 * tile_bytes, preq + 2 * kBN, 2, 2 == ragged_tile); }
     if (nkt > 3) fetch_k(kreq + 3 * tile_bytes, 3, 3 == ragged_tile);
 
-    // ---- this lane's query row (column of S^T) and its Q fragment
-    const int qi = lane & 31, hi = lane >> 5;
-    const int my_row = q_lo + wave * 32 + qi;
-    const bool row_ok = my_row < q_hi;
-    const int ld_row = row_ok ? my_row : q_hi - 1;
+    // ---- the Q fragment of this lane's row
     bf16x8 qf[8];
     {
         const uint16_t* qp = a.q + ((int64_t)ld_row * a.Hq + h) * kHeadDim + 8 * hi;
 #pragma unroll
         for (int t = 0; t < 8; ++t) qf[t] = *(const bf16x8*)(qp + 16 * t);
     }
-    // effective query position: non-causal rows see every real key
-    const int my_qpos = a.causal ? a.q_pos[ld_row] : INT_MAX - 1;   // INT_MAX marks rows past a ragged tail
     int wave_qmin = my_qpos, wave_qmax = my_qpos;
 #pragma unroll
     for (int s = 16; s >= 1; s >>= 1) {
@@ -271,7 +273,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     wave_qmin = __builtin_amdgcn_readfirstlane(wave_qmin);
     wave_qmax = __builtin_amdgcn_readfirstlane(wave_qmax);
     if (lane == 0) { lds_qmm[0][wave] = wave_qmin; lds_qmm[1][wave] = wave_qmax; }
-    __syncthreads();
+    wg_barrier();          // LDS only: the Q loads and tile transfers stay in flight
 
     // ---- tile schedule of this workgroup: n_vis = 1 + last tile some row can see (tiles before it that are
     //      hidden, possible only with unordered positions, are swept fully masked); first_mask = first tile
@@ -309,7 +311,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
             for (int w = 0; w < kPfWaves; ++w) cand[wave][1 + w] = fm[w];
         }
-        __syncthreads();
+        wg_barrier();
         int lv = -1, fmk = nkt;
 #pragma unroll
         for (int sw = 0; sw < kPfWaves; ++sw) {
