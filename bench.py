@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--workload", default="lwm7b", choices=["lwm7b", "long", "mixed"],
                     help="lwm7b = configs[1]+configs[2] (default, the bench line); long = configs[3]; mixed = configs[4]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--retain", action="store_true",
+                    help="proactive retention (scale-down during prefill): while each shard is attended, esp_kv_append keeps "
+                         "ALL its rows in a token pool from a second stream; reports the overhead against prefill alone")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy kernel (known traffic, to scale rocprofv3 --pmc byte counters)")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "bench_lwm7b_hbm_traffic.json"),
@@ -218,7 +221,46 @@ def main():
                                      "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "traffic": None, "launch_ms": ms_decode,
                                      "bytes_per_launch": byts}
         result["config"].update({"decode_B": dc.B, "decode_total_tokens": dc.total_tokens, "pool_slots": dc.num_slots})
-    if args.workload == "lwm7b" and args.traffic_json and os.path.exists(args.traffic_json):
+    if args.retain:
+        # pool with room for every row of every shard, slots = seeded permutation (any token-level placement is legal)
+        n_rows = sum(s.k.shape[0] for s in pc.shards)
+        S = 1 << (n_rows - 1).bit_length()
+        kp = torch.zeros((S, pc.Hkv, pc.D), dtype=torch.bfloat16, device=dev)
+        vp = torch.zeros_like(kp)
+        perm = torch.from_numpy(np.random.default_rng(99).permutation(S)[:n_rows].astype(np.int32)).to(dev)
+        slots, o = [], 0
+        for s in pc.shards:
+            slots.append(perm[o:o + s.k.shape[0]].contiguous()); o += s.k.shape[0]
+        side = torch.cuda.Stream()
+
+        def prefill_only(with_retain):
+            for i, s in enumerate(pc.shards):
+                if with_retain:
+                    side.wait_stream(torch.cuda.current_stream())
+                    with torch.cuda.stream(side):
+                        esp.esp_kv_append(s.k, s.v, slots[i], kp, vp)
+                esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos,
+                                             None if single else pc.cu_q, None if single else s.cu_kv,
+                                             None if single else pc.max_q, None if single else s.max_kv,
+                                             softmax_scale=pc.scale, causal=pc.causal, O=part_O[i], LSE=part_L[i], workspace=ws_pf)
+            if with_retain:
+                torch.cuda.current_stream().wait_stream(side)
+
+        times = {}
+        for mode in (False, True, False, True):
+            prefill_only(mode); torch.cuda.synchronize()
+            e0, e1 = ev(), ev()
+            e0.record()
+            for _ in range(args.steps):
+                prefill_only(mode)
+            e1.record(); torch.cuda.synchronize()
+            times.setdefault(mode, []).append(e0.elapsed_time(e1) / args.steps)
+        t_plain, t_ret = min(times[False]), min(times[True])
+        ok = all(torch.equal(kp[slots[i].long()], s.k) and torch.equal(vp[slots[i].long()], s.v) for i, s in enumerate(pc.shards))
+        result["retain"] = {"ms_prefill_alone": t_plain, "ms_prefill_with_retention": t_ret,
+                            "overhead_pct": 100.0 * (t_ret / t_plain - 1.0), "rows_retained": n_rows,
+                            "bytes_moved": 2 * 2 * n_rows * pc.Hkv * pc.D * 2, "pool_matches": bool(ok)}
+    if args.workload == "lwm7b" and os.path.exists(args.traffic_json):
         tr = json.load(open(args.traffic_json))
         result["roofline"]["traffic"] = tr.get("prefill_kernel")
         if "roofline_decode" in result:
