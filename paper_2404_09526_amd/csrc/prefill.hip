@@ -125,7 +125,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     // each array's base folded into the per-lane register every operand read of the loop needs no address math.
     constexpr int kLdsV = 0, kLdsK = kLdsV + kStages * kTileBytes, kLdsPos = kLdsK + kStages * kKTileBytes,
                   kLdsQmm = kLdsPos + kStages * kBN * 4, kLdsSched = kLdsQmm + 2 * kPfWaves * 4,
-                  kLdsTotal = kLdsSched + kPfWaves * (1 + kPfWaves) * 4;
+                  kLdsFlag = kLdsSched + kPfWaves * (1 + kPfWaves) * 4, kLdsTotal = kLdsFlag + 16;
     __shared__ __attribute__((aligned(1024))) unsigned char smem[kLdsTotal];
     unsigned char (*lds_k)[kKTileBytes] = (unsigned char (*)[kKTileBytes])(smem + kLdsK);
     unsigned char (*lds_v)[kTileBytes] = (unsigned char (*)[kTileBytes])(smem + kLdsV);
@@ -205,36 +205,37 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     const uint32_t lds_base = (uint32_t)(uintptr_t)(ESP_LDS unsigned char*)smem;
     const uint32_t lds_k0 = lds_base + kLdsK, lds_v0 = lds_base + kLdsV, lds_p0 = lds_base + kLdsPos;
 
-    // K tile at kt into K stage st: 2 transfers per wavefront, 3 for wavefront 7.  `tail`: it is the ragged last
-    // tile, whose rows past the end re-read the last row (their scores get masked).
-    auto fetch_k = [&](const char* kt, int st, bool tail) {
+    // K tile at kt into K stage st: 2 transfers per wavefront, 3 for wavefront 7; `part` picks one of them, so that
+    // the sweep can spread them over an iteration (a burst of transfers from all wavefronts at once backs up the
+    // memory pipeline and stalls the issuing wavefronts).  `tail`: it is the ragged last tile, whose rows past the
+    // end re-read the last row (their scores get masked).
+    auto fetch_k_part = [&](const char* kt, int st, bool tail, int part) {
         const uint32_t ko = lds_k0 + st * kKTileBytes;
-        if (__builtin_expect(tail, 0)) {
-            const int last = tail_rows - 1;
-            load_to_lds_b128(ko + 1024 * wave, kt, k_goff(wave, last));
-            load_to_lds_b128(ko + 1024 * (wave + 8), kt, k_goff(wave + 8, last));
-            if (wave == 7) load_to_lds_b128(ko + 1024 * 16, kt, k_goff(16, last));
-        } else {
-            load_to_lds_b128(ko + 1024 * wave, kt, gk0);
-            load_to_lds_b128(ko + 1024 * (wave + 8), kt, gk1);
-            if (wave == 7) load_to_lds_b128(ko + 1024 * 16, kt, gk2);
-        }
+        const int n = part == 0 ? wave : part == 1 ? wave + 8 : 16;
+        if (part == 2 && wave != 7) return;
+        if (__builtin_expect(tail, 0)) load_to_lds_b128(ko + 1024 * n, kt, k_goff(n, tail_rows - 1));
+        else load_to_lds_b128(ko + 1024 * n, kt, part == 0 ? gk0 : part == 1 ? gk1 : gk2);
     };
     // V tile at vt and its positions at pt into V stage st: 2 transfers per wavefront, 3 for wavefront 0
-    auto fetch_v = [&](const char* vt, const int32_t* pt, int st, bool tail) {
+    auto fetch_v_part = [&](const char* vt, const int32_t* pt, int st, bool tail, int part) {
         const uint32_t vo = lds_v0 + st * kTileBytes + wave * 2048;
-        if (__builtin_expect(tail, 0)) {
-            const int last = tail_rows - 1;
-            load_to_lds_b128(vo, vt, v_goff(st_r0, min(st_r0, last)));
-            load_to_lds_b128(vo + 1024, vt, v_goff(st_r1, min(st_r1, last)));
-            if (wave == 0) load_to_lds_b32(lds_p0 + st * (kBN * 4), pt, min(lane, last) * 4);
+        const int last = tail_rows - 1;
+        if (part == 2) {
+            if (wave != 0) return;
+            load_to_lds_b32(lds_p0 + st * (kBN * 4), pt, (tail ? min(lane, last) : lane) * 4);
+        } else if (__builtin_expect(tail, 0)) {
+            const int r = part == 0 ? st_r0 : st_r1;
+            load_to_lds_b128(vo + 1024 * part, vt, v_goff(r, min(r, last)));
         } else {
-            load_to_lds_b128(vo, vt, gv0);
-            load_to_lds_b128(vo + 1024, vt, gv1);
-            if (wave == 0) load_to_lds_b32(lds_p0 + st * (kBN * 4), pt, lane * 4);
+            load_to_lds_b128(vo + 1024 * part, vt, part == 0 ? gv0 : gv1);
         }
     };
-    const bool extra_transfer = wave == 0 || wave == 7;
+    auto fetch_k = [&](const char* kt, int st, bool tail) {
+        fetch_k_part(kt, st, tail, 0); fetch_k_part(kt, st, tail, 1); fetch_k_part(kt, st, tail, 2);
+    };
+    auto fetch_v = [&](const char* vt, const int32_t* pt, int st, bool tail) {
+        fetch_v_part(vt, pt, st, tail, 0); fetch_v_part(vt, pt, st, tail, 1); fetch_v_part(vt, pt, st, tail, 2);
+    };
     // positions past the end of a ragged last tile become INT_MAX, hidden from every query
     auto seal_tail = [&](int st) {
         if (wave == 0 && lane >= tail_rows) lds_pos[st][lane] = INT_MAX;
@@ -254,8 +255,17 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     const int ragged_tile = tail_rows < kBN ? nkt - 1 : -8;          // index of the ragged last tile, if any
     if (nkt > 0) { fetch_k(kreq, 0, 0 == ragged_tile); fetch_v(vreq, preq, 0, 0 == ragged_tile); }
     if (nkt > 1) { fetch_k(kreq + tile_bytes, 1, 1 == ragged_tile); fetch_v(vreq + tile_bytes, preq + kBN, 1, 1 == ragged_tile); }
-    if (nkt > 2) { fetch_k(kreq + 2 * tile_bytes, 2, 2 == ragged_tile); fetch_v(vreq + 2 * tile_bytes, preq + 2 * kBN, 2, 2 == ragged_tile); }
+    if (nkt > 2) fetch_k(kreq + 2 * tile_bytes, 2, 2 == ragged_tile);
     if (nkt > 3) fetch_k(kreq + 3 * tile_bytes, 3, 3 == ragged_tile);
+    // V stage 3 stands in for the tile before the first one (the loop multiplies the last chunk of tile j-1 at the
+    // start of iteration j): zero it, since stale LDS contents could be NaN patterns; V(3) arrives there later
+    {
+        const uint4 z = make_uint4(0u, 0u, 0u, 0u);
+        uint4* dst = (uint4*)(smem + kLdsV + 3 * kTileBytes) + tid * 2;
+        dst[0] = z;
+        dst[1] = z;
+        if (tid == 0) *(int32_t*)(smem + kLdsFlag) = 0;      // "redo with the plain sweep" flag, see below
+    }
 
     // ---- the Q fragment of this lane's row
     bf16x8 qf[8];
@@ -337,32 +347,35 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     for (int db = 0; db < 4; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
-    float m_ref = -INFINITY;   // softmax offset in use (scale*log2(e)*score units), the same in both halves
+    // softmax state.  The offset m_use subtracted from the scaled scores moves in whole steps (so every change
+    // of it rescales by an exact power of two) and only when it has to: lim is the largest tile sum
+    // accepted without a move, -1 while the row has not seen a key yet (m_use is then a stand-in 0).
+    float m_use = 0.f, lim = -1.f;
     float lsum = 0.f;          // running sum of exp2 over this lane's half of the keys
+    float psum = 0.f, p0 = 0.f, p1 = 0.f;
 
     floatx16 sbuf[2][2];       // S^T of two tiles in flight: [tile parity][kvb]
     union PFrag { uint32_t u[4]; bf16x8 v; };
-    PFrag pf[2][2];            // P^T of the current tile packed to bf16: [kvb][t2]
+    PFrag pf[2][2];            // P^T packed to bf16, one fragment per chunk of 16 keys: [kvb][t2]
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pf[c >> 1][c & 1].u[e] = 0u;
     union VFrag { short4_t s[2]; bf16x8 v; };
-    constexpr int kRing = 4;
-    VFrag fr[kRing];           // ring of operand fragments, fetched kRing MFMAs ahead of their use
+    VFrag frk[2], frv[2];      // operand fragments, fetched two steps ahead of their use
 
-    // The 32 MFMAs of an iteration: m = 0..15 is S^T = K Q^T of the next tile, (t, kvb) = (m / 2, m % 2);
-    // m = 16..31 is O^T += V^T P^T of the current tile, (kvb, t2, db) = ((m-16) / 8, ((m-16) / 4) % 2, m % 4);
-    // m = 32..35 are the first fragments of the following iteration (K of the tile after next).
-    auto read_frag = [&](int m, int st_k, int st_k2, int st_v) {
-        if (m < 16 || m >= 32) {
-            const int mm = m & 15, t = mm >> 1, kvb = mm & 1;
-            fr[m % kRing].v = *(const ESP_LDS bf16x8*)(uintptr_t)(k_rd + (m < 16 ? st_k : st_k2) * kKTileBytes + kvb * (32 * kKRow) + t * 32);
-        } else {
-            const int kvb = (m - 16) >> 3, t2 = ((m - 16) >> 2) & 1, db = m & 3;
-            const uint32_t vp = v_rd[db] + st_v * kTileBytes + (32 * kvb + 16 * t2) * 256;
-            fr[m % kRing].s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ESP_LDS short4_t*)(uintptr_t)(vp));
-            fr[m % kRing].s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ESP_LDS short4_t*)(uintptr_t)(vp + 8 * 256));
-        }
+    // K fragment i = (t, kvb) = (i / 2, i % 2) of the tile in K stage st; V^T fragment p = (kvb, t2, db) =
+    // (p / 8, (p / 4) % 2, p % 4) of the tile at byte offset stage_off of the V stages
+    auto read_k = [&](int slot, int st, int i) {
+        frk[slot].v = *(const ESP_LDS bf16x8*)(uintptr_t)(k_rd + st * kKTileBytes + (i & 1) * (32 * kKRow) + (i >> 1) * 32);
+    };
+    auto read_v = [&](int slot, uint32_t stage_off, int p) {
+        const uint32_t vp = v_rd[p & 3] + stage_off + (32 * (p >> 3) + 16 * ((p >> 2) & 1)) * 256;
+        frv[slot].s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ESP_LDS short4_t*)(uintptr_t)(vp));
+        frv[slot].s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ESP_LDS short4_t*)(uintptr_t)(vp + 8 * 256));
     };
 
-    // mask of tile j: key positions in lds_pos[st] against this lane's query position
+    // mask of a tile: key positions in lds_pos[st] against this lane's query position
     auto apply_mask = [&](floatx16 (&sc)[2], int st) {
 #pragma unroll
         for (int kvb = 0; kvb < 2; ++kvb)
@@ -375,112 +388,143 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
                 if (kp.w > my_qpos) sc[kvb][4 * bb + 3] = -INFINITY;
             }
     };
-
-    float psum, m_use;
-    // probabilities of score pair c (0..15) of the current tile: exp2, fp32 partial sum (of the unrounded
-    // values: the log-sum-exp has to be good to 1e-4), bf16 pack
-    auto prob_pair = [&](const floatx16 (&sc)[2], int c) {
-        const int kvb = c >> 3, r = 2 * (c & 7);
-        const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[kvb][r], a.scale_log2, -m_use));
-        const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[kvb][r + 1], a.scale_log2, -m_use));
-        psum += p0;
-        psum += p1;
-        const uint32_t pk = pack_bf16(p0, p1);
-        asm volatile("" :: "v"(pk));   // pack here, among the MFMAs of S^T, not in a bunch in front of the PV product
-        pf[kvb][(c & 7) >> 2].u[c & 3] = pk;
+    // largest score of this lane's query row in a tile, in exp2 units (-inf if every key is masked)
+    auto row_max = [&](const floatx16 (&sc)[2]) {
+        float tmax = sc[0][0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, sc[0][r]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sc[1][r]);
+        return half_swap_max(tmax) * a.scale_log2;
     };
 
-    const int mask_from = min(first_mask, tail_rows < kBN ? nkt - 1 : nkt);   // first tile this wavefront masks
-    const char* k_next = kreq + 4 * tile_bytes;                       // K tile that iteration 0 fetches
-    const char* v_next = vreq + 3 * tile_bytes;                       // V tile that iteration 0 fetches
-    const int32_t* p_next = preq + 3 * kBN;
+    // probabilities of score pair c (0..15) of the current tile, in two parts placed behind the two MFMAs of a
+    // step: exp2 first, then the fp32 partial sum (of the unrounded values: the log-sum-exp has to be good to
+    // 1e-4) and the bf16 pack
+    auto pair_exp = [&](const floatx16 (&sc)[2], int c) {
+        const int kvb = c >> 3, r = 2 * (c & 7);
+        p0 = __builtin_amdgcn_exp2f(fmaf(sc[kvb][r], a.scale_log2, -m_use));
+        p1 = __builtin_amdgcn_exp2f(fmaf(sc[kvb][r + 1], a.scale_log2, -m_use));
+    };
+    auto pair_sum_pack = [&](int c) {
+        if (c == 0) psum = p0 + p1;
+        else { psum += p0; psum += p1; }
+        const uint32_t pk = pack_bf16(p0, p1);
+        asm volatile("" :: "v"(pk), "v"(psum));   // sum and pack here, not in a bunch further down
+        pf[c >> 3][(c >> 2) & 1].u[c & 3] = pk;
+    };
 
-    // One tile, in two halves separated by workgroup barriers; wavefronts 4-7 run half an iteration behind
-    // wavefronts 0-3 (one extra barrier before their loop, one after the loop of the others).
-    // On entry: scores of tile j in sbuf[PAR], the first kRing K fragments of tile j+1 in fr.
-    // The exp2 work of tile j is interleaved with S^T of tile j+1 (into sbuf[PAR^1]); then O^T += V^T P^T of
-    // tile j, with the fetch of K(j+4), V(j+3) and the first K fragments of tile j+2 issued among its MFMAs.
-    // LDS stages: K(t), V(t) and the positions of tile t live in stage t % 4.  K(j) is dead during iteration j
-    // (S^T of tile j was finished before the previous barrier), so K(j+4) may overwrite it; V(j+3) overwrites
-    // V(j-1); both were last read at least one barrier earlier by either group.  What a wavefront fetched in its
-    // iteration j-1 has landed before the barrier that ends its iteration j; the first reads of those tiles come
-    // at least one further barrier later, by which time the other group has passed the same point.
-    auto iteration = [&](auto st_c, auto par_c, int j) {
-        constexpr int ST = decltype(st_c)::value, PAR = decltype(par_c)::value;
-        constexpr int ST1 = (ST + 1) % kStages, ST2 = (ST + 2) % kStages, ST3 = (ST + 3) % kStages;
-        floatx16 (&sc)[2] = sbuf[PAR];
-        floatx16 (&sn)[2] = sbuf[PAR ^ 1];
-        if (j >= mask_from) apply_mask(sc, ST);
-        m_use = (m_ref == -INFINITY) ? 0.f : m_ref;
-        psum = 0.f;
-#pragma unroll
-        for (int m = 0; m < 16; ++m) {                // S^T of tile j+1 (after the last tile: stale data, unused)
-            const int t = m >> 1, kvb = m & 1;
-            if (t == 0) {
-                floatx16 zero;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) zero[r] = 0.f;
-                sn[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[m % kRing].v, qf[t], zero, 0, 0, 0);
-            } else {
-                sn[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[m % kRing].v, qf[t], sn[kvb], 0, 0, 0);
-            }
-            read_frag(m + kRing, ST1, ST2, ST);       // the slot is free again
-            prob_pair(sc, m);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        // offset refresh (rare): first visible key of a row, or a sum that shows the offset fell far behind
-        const bool redo = (m_ref == -INFINITY) || !(psum <= kSumLimit);
-        if (__builtin_amdgcn_ballot_w64(redo) != 0) {
-            float tmax = sc[0][0];
-#pragma unroll
-            for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, sc[0][r]);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sc[1][r]);
-            tmax = half_swap_max(tmax) * a.scale_log2;
-            const float m_new = fmaxf(m_ref, tmax);
-            const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_ref - m_new);
-            m_ref = m_new;
+    // End of a tile in the pipelined sweep.  The probabilities were taken against the offset in use, without
+    // looking at the scores first; that is exact as long as nothing left the range of fp32 / bf16, whatever their
+    // size.  The tile sum tells: up to lim nothing needs doing (the common case: one compare); above it the
+    // offset moves up to the tile's row maximum, and everything accumulated so far (the sum, O^T, and the last
+    // chunk's P^T, which is multiplied only in the next iteration) is rescaled by the exact power of two.  A sum
+    // that is not finite or beyond 2^100, or a first visible tile whose maximum is further than 2^64 from the
+    // stand-in offset, means the optimistic pass cannot be trusted: the workgroup then redoes its rows with the
+    // plain sweep below (`unsafe` is only ever set, never cleared).
+    int32_t* lds_unsafe = (int32_t*)(smem + kLdsFlag);
+    auto close_tile = [&](const floatx16 (&sc)[2]) {
+        lsum += psum;
+        if (__builtin_amdgcn_ballot_w64(!(psum <= lim)) != 0) {
+            const float tm = row_max(sc);
+            const bool move = !(psum <= lim) && tm != -INFINITY;     // a fresh row whose tile is all masked stays fresh
+            const bool bad = move && (!(psum <= 0x1p100f) || (lim < 0.f && !(fabsf(tm) <= 64.f)));
+            if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0) *lds_unsafe = 1;
+            const float m_new = move ? m_use + ceilf(tm - m_use) : m_use;     // whole steps: alpha is a power of two
+            const float alpha = __builtin_amdgcn_exp2f(m_use - m_new);        // 1 where nothing moves
+            m_use = m_new;
+            if (move) lim = kSumLimit;
             lsum *= alpha;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-            m_use = (m_ref == -INFINITY) ? 0.f : m_ref;   // still nothing visible: exp2(-inf - 0) = 0
-            psum = 0.f;
 #pragma unroll
-            for (int c = 0; c < 16; ++c) prob_pair(sc, c);
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t w = pf[1][1].u[e];
+                pf[1][1].u[e] = pack_bf16(bf16_lo(w) * alpha, bf16_hi(w) * alpha);
+            }
         }
-        lsum += psum;
-        __builtin_amdgcn_sched_barrier(0);
-        // half-iteration boundary: the other wavefront of this SIMD is half an iteration away, so that the
-        // vector-heavy half of one runs beside the MFMA-only half of the other
-        asm volatile("s_barrier" :: "v"(sn[0]), "v"(sn[1]), "v"(pf[0][0].v), "v"(pf[0][1].v), "v"(pf[1][0].v), "v"(pf[1][1].v), "v"(lsum) : "memory");
-        const bool do_k = j < n_vis - 4, do_v = j < n_vis - 3;
-#pragma unroll
-        for (int m = 16; m < 32; ++m) {               // O^T += V^T P^T of tile j
-            const int kvb = (m - 16) >> 3, t2 = ((m - 16) >> 2) & 1, db = m & 3;
-            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[m % kRing].v, pf[kvb][t2].v, oacc[db], 0, 0, 0);
-            read_frag(m + kRing, ST1, ST2, ST);
-            if (m == 19 && do_k) fetch_k(k_next, ST, j + 4 == ragged_tile);
-            if (m == 23 && do_v) fetch_v(v_next, p_next, ST3, j + 3 == ragged_tile);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        k_next += tile_bytes; v_next += tile_bytes; p_next += kBN;
-        // what iteration j-1 fetched must have landed; this iteration's own transfers may stay in flight
-        if (do_k) { if (extra_transfer) wait_vm<5>(); else wait_vm<4>(); }
-        else wait_vm<0>();
-        if (__builtin_expect(j + 2 == ragged_tile, 0)) seal_tail(ST2);   // its positions landed with V(j+2)
-        asm volatile("s_barrier"
-                     :: "v"(sn[0]), "v"(sn[1]), "v"(oacc[0]), "v"(oacc[1]), "v"(oacc[2]), "v"(oacc[3]) : "memory");
     };
 
-    // ---- prologue: K(0..3), V(0..2) were requested at kernel entry; S^T of tile 0, first K fragments of tile 1
+    const int mask_from = min(first_mask, tail_rows < kBN ? nkt - 1 : nkt);   // first tile this wavefront masks
+    const char* k_next = kreq + 4 * tile_bytes;                       // K tile that iteration 0 fetches
+    const char* v_next = vreq + 2 * tile_bytes;                       // V tile that iteration 0 fetches
+    const int32_t* p_next = preq + 2 * kBN;
+
+    // One tile per iteration, one workgroup barrier at its end; every wavefront runs the same uniform stream of
+    // 16 steps, each with two MFMAs and one score pair:
+    //   step m:  S^T MFMA m of tile j+1 (into sbuf[PAR^1]);  exp2 of pair m of tile j;
+    //            O^T MFMA p = (m + 12) % 16;                 sum and pack of pair m
+    // The O^T MFMAs trail the pairs by four steps, i.e. by one chunk of 16 keys: chunk c of tile j is multiplied
+    // in steps 4c+4 .. 4c+7, and the last chunk in steps 0 .. 3 of iteration j+1 (after the loop for the last
+    // tile).  With two wavefronts per SIMD, each issuing an instruction about every 6-8 cycles, this keeps an
+    // MFMA (32 cycles) in front of every 5-6 other instructions of both wavefronts.
+    // On entry: scores of tile j in sbuf[PAR]; frk = K fragments 0, 1 of tile j+1; frv = V^T fragments 12, 13
+    // of tile j-1; pf[1][1] = last chunk of tile j-1 (zeros, and a zeroed V stage, when j = 0).
+    // LDS stages: K(t), V(t) and the positions of tile t live in stage t % 4.  Iteration j reads K(j+1), the
+    // first two fragments of K(j+2), V(j-1) (steps 0, 1) and V(j); it fetches K(j+4) over K(j), last read in
+    // iteration j-1, and V(j+2) over V(j-2), last read in the first steps of iteration j-1: both before the
+    // barrier that ended iteration j-1.  What a wavefront fetched in iteration j-1 has landed before the barrier
+    // that ends its iteration j, and is first read in iteration j+1.
+    auto iteration = [&](auto st_c, auto par_c, auto plain_c, int j) {
+        constexpr int ST = decltype(st_c)::value, PAR = decltype(par_c)::value;
+        constexpr bool PLAIN = decltype(plain_c)::value != 0;
+        constexpr int ST1 = (ST + 1) % kStages, ST2 = (ST + 2) % kStages, ST3 = (ST + 3) % kStages;
+        floatx16 (&sc)[2] = sbuf[PAR];
+        floatx16 (&sn)[2] = sbuf[PAR ^ 1];
+        if (!PLAIN && j >= mask_from) apply_mask(sc, ST);
+        const bool do_k = PLAIN || j < n_vis - 4, do_v = PLAIN || j < n_vis - 2;
+        const bool tail_k = !PLAIN && j + 4 == ragged_tile, tail_v = !PLAIN && j + 2 == ragged_tile;
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+            const int t = m >> 1, kvb = m & 1;
+            if (t == 0) {                                 // S^T of tile j+1 (after the last tile: stale data, unused)
+                floatx16 zero;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+                sn[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frk[m & 1].v, qf[t], zero, 0, 0, 0);
+            } else {
+                sn[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frk[m & 1].v, qf[t], sn[kvb], 0, 0, 0);
+            }
+            pair_exp(sc, m);
+            __builtin_amdgcn_sched_barrier(0);
+            const int p = (m + 12) & 15;                  // O^T += V^T P^T, one chunk behind the pairs
+            oacc[p & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frv[m & 1].v, pf[p >> 3][(p >> 2) & 1].v, oacc[p & 3], 0, 0, 0);
+            // both fragments of step m+2; the K fragment last, so that the wait in front of its MFMA covers the
+            // V^T fragment too (LDS reads return in order) and one wait per step is enough
+            read_v(m & 1, (m < 2 ? ST3 : ST) * kTileBytes, (m + 14) & 15);
+            read_k(m & 1, m + 2 < 16 ? ST1 : ST2, (m + 2) & 15);
+            pair_sum_pack(m);
+            // the transfers of this iteration, spread out (a burst from all wavefronts at once backs up the memory
+            // pipeline); the odd ones of wavefronts 7 and 0 go first, so that "all but the last four have landed"
+            // is the same wait for every wavefront
+            if (m == 1) {
+                if (do_k) fetch_k_part(k_next, ST, tail_k, 2);
+                if (do_v) fetch_v_part(v_next, p_next, ST2, tail_v, 2);
+            }
+            if (do_k && (m == 3 || m == 6)) fetch_k_part(k_next, ST, tail_k, m / 6);
+            if (do_v && (m == 9 || m == 12)) fetch_v_part(v_next, p_next, ST2, tail_v, m / 12);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        close_tile(sc);
+        k_next += tile_bytes; v_next += tile_bytes; p_next += kBN;
+        // what iteration j-1 fetched must have landed; this iteration's own transfers may stay in flight
+        if (do_k) wait_vm<4>();
+        else if (do_v) wait_vm<2>();
+        else wait_vm<0>();
+        if (__builtin_expect(j + 1 == ragged_tile, 0)) seal_tail(ST1);   // its positions landed with V(j+1)
+        asm volatile("s_barrier" :: "v"(sn[0]), "v"(sn[1]), "v"(oacc[0]), "v"(oacc[1]), "v"(oacc[2]), "v"(oacc[3]),
+                                    "v"(pf[1][1].v) : "memory");
+    };
+
+    // ---- prologue: K(0..3), V(0), V(1) were requested at kernel entry; S^T of tile 0, first fragments
     wait_vm<0>();
-    if (ragged_tile >= 0 && ragged_tile < 3) seal_tail(ragged_tile);
+    if (ragged_tile >= 0 && ragged_tile < 2) seal_tail(ragged_tile);
     wg_barrier();
     if (n_vis > 0) {
-#pragma unroll
-        for (int m = 0; m < kRing; ++m) read_frag(m, 0, 0, 0);
+        read_k(0, 0, 0);
+        read_k(1, 0, 1);
 #pragma unroll
         for (int m = 0; m < 16; ++m) {
             const int t = m >> 1, kvb = m & 1;
@@ -488,21 +532,104 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) sbuf[0][kvb][r] = 0.f;
             }
-            sbuf[0][kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[m % kRing].v, qf[t], sbuf[0][kvb], 0, 0, 0);
-            if (m + kRing < 16) read_frag(m + kRing, 0, 0, 0);
+            sbuf[0][kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frk[m & 1].v, qf[t], sbuf[0][kvb], 0, 0, 0);
+            read_k(m & 1, m + 2 < 16 ? 0 : 1, (m + 2) & 15);        // ends with fragments 0, 1 of tile 1 (stale if absent)
         }
+        read_v(0, 3 * kTileBytes, 12);                              // the zeroed stage: there is no tile -1
+        read_v(1, 3 * kTileBytes, 13);
+        // the offset starts at the exact row maximum of tile 0 wherever the row sees a key there (with ascending
+        // positions: whenever it sees any key at all), so that the largest probability of a short row is exactly 1
+        // and takes no bf16 rounding; rows still without a key keep the stand-in 0
+        if (0 >= mask_from) apply_mask(sbuf[0], 0);
+        const float tm0 = row_max(sbuf[0]);
+        if (tm0 != -INFINITY) { m_use = tm0; lim = kSumLimit; }
+    }
+    // the sweep: a loop with a single exit over groups of four tiles (the stage of a tile is a compile-time
+    // constant), then the zero to three tiles left over
+    //   1. "plain" iterations: every transfer is a full tile that exists and this wavefront masks nothing, so the
+    //      stream has no conditional code at all (a wavefront may leave this part earlier than its neighbours:
+    //      the barriers and transfers per iteration are the same in both kinds);
+    //   2. general iterations for the rest, again in groups of four, then one by one.
+    const int n_plain = max(0, min(min(n_vis - 4, mask_from), ragged_tile >= 0 ? nkt - 5 : INT_MAX)) & ~3;
+    int j = 0;
+    for (; j < n_plain; j += 4) {
+        iteration(IC<0>{}, IC<0>{}, IC<1>{}, j);
+        iteration(IC<1>{}, IC<1>{}, IC<1>{}, j + 1);
+        iteration(IC<2>{}, IC<0>{}, IC<1>{}, j + 2);
+        iteration(IC<3>{}, IC<1>{}, IC<1>{}, j + 3);
+    }
+    for (; j + 4 <= n_vis; j += 4) {
+        iteration(IC<0>{}, IC<0>{}, IC<0>{}, j);
+        iteration(IC<1>{}, IC<1>{}, IC<0>{}, j + 1);
+        iteration(IC<2>{}, IC<0>{}, IC<0>{}, j + 2);
+        iteration(IC<3>{}, IC<1>{}, IC<0>{}, j + 3);
+    }
+    if (j < n_vis) {
+        iteration(IC<0>{}, IC<0>{}, IC<0>{}, j);
+        if (j + 1 < n_vis) {
+            iteration(IC<1>{}, IC<1>{}, IC<0>{}, j + 1);
+            if (j + 2 < n_vis) iteration(IC<2>{}, IC<0>{}, IC<0>{}, j + 2);
+        }
+    }
+    if (n_vis > 0) {                                                // last chunk of the last tile
+        const uint32_t last_off = (uint32_t)((n_vis - 1) & 3) * kTileBytes;
 #pragma unroll
-        for (int m = 0; m < kRing; ++m) read_frag(m, 1, 1, 0);      // K fragments of tile 1 (stale if absent)
+        for (int m = 0; m < 4; ++m) {
+            oacc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frv[m & 1].v, pf[1][1].v, oacc[m], 0, 0, 0);
+            if (m < 2) read_v(m & 1, last_off, 14 + m);
+        }
     }
-    const bool group_b = wave >= kPfWaves / 2;     // wavefronts w and w + 4 share a SIMD
-    if (group_b) asm volatile("s_barrier" ::: "memory");
-    for (int j = 0; j < n_vis;) {
-        iteration(IC<0>{}, IC<0>{}, j); if (++j >= n_vis) break;
-        iteration(IC<1>{}, IC<1>{}, j); if (++j >= n_vis) break;
-        iteration(IC<2>{}, IC<0>{}, j); if (++j >= n_vis) break;
-        iteration(IC<3>{}, IC<1>{}, j); ++j;
+
+    // ---- the plain sweep, for a workgroup whose optimistic pass met scores outside its range: one tile at a
+    //      time through stage 0, row maximum before the exponentials, nothing overlapped.  Slow and exact.
+    float m_fin = m_use;
+    wg_barrier();                                                   // everyone's flag write and last LDS reads are done
+    if (__builtin_amdgcn_readfirstlane(*lds_unsafe) != 0) {
+        float m_ref = -INFINITY;
+        lsum = 0.f;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
+        for (int t = 0; t < n_vis; ++t) {
+            wg_barrier();
+            fetch_k(kreq + (int64_t)t * tile_bytes, 0, t == ragged_tile);
+            fetch_v(vreq + (int64_t)t * tile_bytes, preq + t * kBN, 0, t == ragged_tile);
+            wait_vm<0>();
+            if (t == ragged_tile) seal_tail(0);
+            wg_barrier();
+            floatx16 (&sc)[2] = sbuf[0];
+#pragma unroll
+            for (int m = 0; m < 16; ++m) {
+                const int tt = m >> 1, kvb = m & 1;
+                if (tt == 0) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) sc[kvb][r] = 0.f;
+                }
+                read_k(0, 0, m);
+                sc[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frk[0].v, qf[tt], sc[kvb], 0, 0, 0);
+            }
+            apply_mask(sc, 0);
+            const float m_new = fmaxf(m_ref, row_max(sc));
+            const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_ref - m_new);
+            m_ref = m_new;
+            lsum *= alpha;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+            m_use = (m_ref == -INFINITY) ? 0.f : m_ref;             // nothing visible yet: exp2(-inf - 0) = 0
+#pragma unroll
+            for (int c = 0; c < 16; ++c) { pair_exp(sc, c); pair_sum_pack(c); }
+            lsum += psum;
+#pragma unroll
+            for (int p = 0; p < 16; ++p) {
+                read_v(0, 0, p);
+                oacc[p & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frv[0].v, pf[p >> 3][(p >> 2) & 1].v, oacc[p & 3], 0, 0, 0);
+            }
+        }
+        m_fin = m_use;
     }
-    if (!group_b) asm volatile("s_barrier" ::: "memory");
 
     // ---- epilogue: normalise, write O (bf16) and LSE (natural log)
     const float ltot = half_swap_sum(lsum);
@@ -519,7 +646,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
                 *(uint2*)(op + 32 * db + 8 * bb) = w;
             }
         if (hi == 0)
-            a.LSE[(int64_t)my_row * a.Hq + h] = ltot > 0.f ? (m_ref + __builtin_amdgcn_logf(ltot)) * kLn2 : -INFINITY;
+            a.LSE[(int64_t)my_row * a.Hq + h] = ltot > 0.f ? (m_fin + __builtin_amdgcn_logf(ltot)) * kLn2 : -INFINITY;
     }
 }
 
