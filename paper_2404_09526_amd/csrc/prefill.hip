@@ -8,22 +8,26 @@
 //     and keeps their Q fragment (B operand), the softmax state and the fp32 output accumulator
 //     in registers for the whole KV sweep;
 //   * K/V tiles of 64 rows are fetched straight from global memory into a 4-stage LDS ring
-//     (global_load ... lds, no register staging), three tiles ahead of their use;
+//     (global_load ... lds, no register staging), K four tiles and V two tiles ahead of their use;
 //   * the K tile is the A operand of S^T = K Q^T, so a lane ends up with scores of ONE query
 //     row (its column); P^T stays in registers and is the B operand of O^T = V^T P^T, whose A
 //     operand comes from transposing LDS reads of the row-major V tile;
 //   * LDS rows of K are padded to 272 bytes and the 16-byte chunks of V rows are XOR-swizzled, so
 //     that the operand reads spread over all banks;
-//   * one instruction stream per wavefront, software pipelined: the MFMAs of S^T for tile j+1
-//     are interleaved with the exp2 / sum / bf16-pack work of tile j (a wavefront issues one
-//     instruction about every 8 cycles and a 32x32x16 MFMA lasts 32, so with two wavefronts per
-//     SIMD up to ~8 vector instructions fit behind every MFMA), then O^T += V^T P^T of tile j;
-//   * the softmax offset is refreshed only when needed (first visible key, or a probability sum
-//     that shows the offset has fallen more than 2^20 behind), so the common path has no max
-//     reduction and no rescale of the accumulator;
-//   * per (wavefront, KV tile) the minimum / maximum positions decide: tiles past the last one
-//     any row can see are never fetched; tiles below every row need no mask code; else the
-//     element-wise test kv_pos <= q_pos runs.
+//   * one uniform instruction stream per wavefront, software pipelined at the level of single
+//     MFMAs: every step issues one MFMA of S^T for tile j+1, the exp2 of two scores of tile j,
+//     one MFMA of O^T += V^T P^T that trails the probabilities by one chunk of 16 keys, and the
+//     sum / bf16 pack of the two probabilities.  A wavefront issues an instruction only every
+//     6-8 cycles and a 32x32x16 MFMA lasts 32, so with the two wavefronts of a SIMD running the
+//     same mix the matrix pipe always has an MFMA of one of them to run;
+//   * the softmax offset is optimistic: probabilities are taken against the offset in use
+//     without looking at the scores first; one compare per tile on the probability sum tells
+//     whether the offset has to move (exact rescale by a power of two), and a workgroup whose
+//     scores leave the range this can handle redoes its rows with a plain, exact sweep;
+//   * the minimum / maximum position of every KV tile (found by the workgroup itself while its
+//     first tiles are in flight) decide: tiles past the last one any row can see are never
+//     processed; tiles below every row of a wavefront run the branch-free "plain" iteration;
+//     the others apply the element-wise test kv_pos <= q_pos.
 #include <limits.h>
 
 #include "esp_common.h"
@@ -40,38 +44,18 @@ constexpr int kKTileBytes = kBN * kKRow;         // 17 KiB = 17 transfers of 1 K
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4_t;
 #define ESP_LDS __attribute__((address_space(3)))
 
-static int32_t prefill_kv_tiles_bound(int32_t Tkv, int32_t batch) { return Tkv / kBN + batch; }
 static int32_t prefill_q_tiles_bound(int32_t Tq, int32_t batch) { return Tq / kBM + batch; }
 
+// The prefill path keeps nothing in global scratch memory any more; a minimal block stays reserved so that
+// callers written against the workspace contract keep working.
 size_t prefill_workspace_bytes(int32_t Tq, int32_t Tkv, int32_t batch, int32_t Hq, int32_t Hkv) {
-    (void)Tq; (void)Hq; (void)Hkv;
-    return (size_t)prefill_kv_tiles_bound(Tkv, batch) * sizeof(int2) + 256;
-}
-
-// min / max position of every 64-row KV tile of every request: tile_mm[first_tile(r) + t]
-__global__ __launch_bounds__(64) void kv_tile_minmax_kernel(const int32_t* __restrict__ kv_pos,
-                                                            const int32_t* __restrict__ cu_kv, int32_t Tkv,
-                                                            int2* __restrict__ tile_mm) {
-    const int r = blockIdx.y, t = blockIdx.x, lane = threadIdx.x;
-    int first = 0;
-    for (int i = 0; i < r; ++i) first += (cu_kv[i + 1] - cu_kv[i] + kBN - 1) / kBN;
-    const int lo = cu_kv ? cu_kv[r] : 0, hi = cu_kv ? cu_kv[r + 1] : Tkv;
-    if (t >= (hi - lo + kBN - 1) / kBN) return;
-    int row = lo + t * kBN + lane;
-    int mn = INT_MAX, mx = INT_MIN;
-    if (row < hi) mn = mx = kv_pos[row];
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) {
-        mn = min(mn, __shfl_xor(mn, s));
-        mx = max(mx, __shfl_xor(mx, s));
-    }
-    if (lane == 0) tile_mm[first + t] = make_int2(mn, mx);
+    (void)Tq; (void)Tkv; (void)batch; (void)Hq; (void)Hkv;
+    return 256;
 }
 
 struct PrefillArgs {
     const uint16_t* q; const uint16_t* k; const uint16_t* v;
     const int32_t* q_pos; const int32_t* kv_pos; const int32_t* cu_q; const int32_t* cu_kv;
-    const int2* tile_mm;
     uint16_t* O; float* LSE;
     int32_t batch, Tq, Tkv, Hq, Hkv, causal;
     float scale_log2;
@@ -153,7 +137,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         }
     }
     const int kvh = h / G;
-    int q_lo, q_hi, kv_lo, kv_hi, tile0;   // rows of this query tile; rows and first KV tile of its request
+    int q_lo, q_hi, kv_lo, kv_hi;   // rows of this query tile; rows of its request in the shard
     {
         int total = 0;
         for (int r = 0; r < a.batch; ++r) {
@@ -162,21 +146,18 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         }
         if (rank >= total) return;
         int tl = total - 1 - rank;   // later tiles of a causal request see more keys: run them first
-        int r = 0, first_kv_tile = 0;
+        int r = 0;
         for (;; ++r) {
             int len = a.cu_q ? a.cu_q[r + 1] - a.cu_q[r] : a.Tq;
             int nt = (len + kBM - 1) / kBM;
             if (tl < nt) break;
             tl -= nt;
-            int kvlen = a.cu_kv ? a.cu_kv[r + 1] - a.cu_kv[r] : a.Tkv;
-            first_kv_tile += (kvlen + kBN - 1) / kBN;
         }
         const int qs = a.cu_q ? a.cu_q[r] : 0, qe = a.cu_q ? a.cu_q[r + 1] : a.Tq;
         q_lo = qs + tl * kBM;
         q_hi = min(q_lo + kBM, qe);
         kv_lo = a.cu_kv ? a.cu_kv[r] : 0;
         kv_hi = a.cu_kv ? a.cu_kv[r + 1] : a.Tkv;
-        tile0 = first_kv_tile;
     }
     const int kv_len = kv_hi - kv_lo;
     const int nkt = (kv_len + kBN - 1) / kBN;
@@ -267,6 +248,37 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         if (tid == 0) *(int32_t*)(smem + kLdsFlag) = 0;      // "redo with the plain sweep" flag, see below
     }
 
+    // ---- smallest / largest key position of KV tile t of this request, found by one thread: 16 loads of four
+    //      positions when the request's positions are 16-byte aligned and the tile is full, one position at a
+    //      time (index clamped to the last row) otherwise.  The loads of this thread's first tile are issued here,
+    //      ahead of the barrier below, so that their latency overlaps the Q loads.
+    const bool pos_vec_ok = (((uintptr_t)preq) & 15) == 0;
+    auto tile_bounds = [&](int t) {
+        int mn = INT_MAX, mx = INT_MIN;                             // beyond the end: hidden, needs no mask
+        if (t < nkt) {
+            if (pos_vec_ok && (t + 1) * kBN <= kv_len) {
+                const int4* pp = (const int4*)(preq + t * kBN);
+                int4 v[16];
+#pragma unroll
+                for (int e = 0; e < 16; ++e) v[e] = pp[e];
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    mn = min(min(mn, v[e].x), min(v[e].y, min(v[e].z, v[e].w)));
+                    mx = max(max(mx, v[e].x), max(v[e].y, max(v[e].z, v[e].w)));
+                }
+            } else {
+                for (int e = 0; e < kBN; ++e) {
+                    const int pv = preq[min(t * kBN + e, kv_len - 1)];
+                    mn = min(mn, pv);
+                    mx = max(mx, pv);
+                }
+            }
+        }
+        return make_int2(mn, mx);
+    };
+    int2 mm_first = make_int2(INT_MAX, INT_MIN);
+    if (a.causal) mm_first = tile_bounds(tid);
+
     // ---- the Q fragment of this lane's row
     bf16x8 qf[8];
     {
@@ -303,9 +315,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
         for (int w = 0; w < kPfWaves; ++w) fm[w] = nkt;
         for (int t0 = wave * 64; t0 < nkt; t0 += kPfWaves * 64) {
-            const int t = t0 + lane;
-            int2 mm = make_int2(INT_MAX, INT_MIN);                  // beyond the end: hidden, needs no mask
-            if (t < nkt) mm = a.tile_mm[tile0 + t];
+            const int2 mm = t0 == wave * 64 ? mm_first : tile_bounds(t0 + lane);
             const uint64_t vis = __builtin_amdgcn_ballot_w64(mm.x <= wg_qmax);
             if (vis) last_vis = t0 + 63 - __builtin_clzll(vis);
 #pragma unroll
@@ -655,17 +665,10 @@ esp_status launch_prefill(const void* q, const void* k, const void* v, const int
                           int32_t max_q, int32_t max_kv, int32_t Hq, int32_t Hkv, float softmax_scale,
                           int32_t causal, void* O, float* LSE, void* workspace, size_t workspace_bytes,
                           hipStream_t stream) {
-    (void)workspace_bytes; (void)max_q;
-    int2* tile_mm = (int2*)workspace;
-    if (causal && Tkv > 0 && max_kv > 0) {
-        dim3 grid((max_kv + kBN - 1) / kBN, batch);
-        hipLaunchKernelGGL(kv_tile_minmax_kernel, grid, dim3(64), 0, stream, kv_pos, cu_kv, Tkv, tile_mm);
-        esp_status st = check_launch("kv_tile_minmax_kernel");
-        if (st != ESP_OK) return st;
-    }
+    (void)workspace; (void)workspace_bytes; (void)max_q; (void)max_kv;
     PrefillArgs a;
     a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
-    a.q_pos = q_pos; a.kv_pos = kv_pos; a.cu_q = cu_q; a.cu_kv = cu_kv; a.tile_mm = tile_mm;
+    a.q_pos = q_pos; a.kv_pos = kv_pos; a.cu_q = cu_q; a.cu_kv = cu_kv;
     a.O = (uint16_t*)O; a.LSE = LSE;
     a.batch = batch; a.Tq = Tq; a.Tkv = Tkv; a.Hq = Hq; a.Hkv = Hkv; a.causal = causal ? 1 : 0;
     a.scale_log2 = softmax_scale * kLog2e;
