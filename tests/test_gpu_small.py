@@ -281,3 +281,27 @@ def test_prefill_large_scores_refresh_the_softmax_offset(esp, cuda):
     pc2 = wl.contiguous_prefill("sink-first", 64, 1000, [(0, 640)], 4, 4, 29, cuda, causal=False)
     pc2.shards[0].k[3:5] *= 60.0  # the huge scores come first, everything later is ~2^-80 of them
     run_prefill_case(esp, pc2)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("causal", [False, True])
+def test_prefill_scores_beyond_the_optimistic_range_take_the_exact_sweep(esp, cuda, causal):
+    """A key whose score lies ~2^400 above every earlier one, for every query row, arriving in a late tile: the
+    probabilities of the pipelined pass overflow there, so the kernel must notice and redo the rows with its plain
+    sweep (a result from the optimistic pass alone would be NaN or far off).  Also a row set whose scores all lie
+    ~2^300 below zero, where a probability taken against the stand-in offset underflows.  Ragged tail included."""
+    Tq, Tkv = 300, 1000
+    pc = wl.contiguous_prefill("overflow", Tq, 1000, [(0, Tkv)], 4, 2, 41, cuda, causal=causal)
+    s = pc.shards[0]
+    u = torch.ones(pc.D, dtype=torch.bfloat16, device=cuda)
+    pc.q[:] = (pc.q.float() * 0.05 + 1.5).to(torch.bfloat16)      # every row close to 1.5 * u
+    s.k[:] = (s.k.float() * 0.05).to(torch.bfloat16)
+    s.k[777] = 16.0 * u                                            # score 1.5*16*128*scale = 271 nats above the rest
+    s.k[990] = 15.5 * u                                            # close second, in the ragged last tile
+    run_prefill_case(esp, pc)
+    pc2 = wl.contiguous_prefill("underflow", Tq, 1000, [(0, Tkv)], 4, 2, 42, cuda, causal=causal)
+    s2 = pc2.shards[0]
+    pc2.q[:] = (pc2.q.float() * 0.05 + 1.5).to(torch.bfloat16)
+    s2.k[:] = (s2.k.float() * 0.05 - 12.0).to(torch.bfloat16)      # every score about -200 nats
+    s2.k[100:104] = (s2.k[100:104].float() + 24.0).to(torch.bfloat16)   # a few keys 400 nats above those, in tile 1
+    run_prefill_case(esp, pc2)
