@@ -639,13 +639,17 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
             }
         }
         m_fin = m_use;
+        wg_barrier();                                               // the epilogue reuses the K stages
     }
 
     // ---- epilogue: normalise, write O (bf16) and LSE (natural log)
     const float ltot = half_swap_sum(lsum);
     const float inv = ltot > 0.f ? 1.0f / ltot : 0.f;
-    if (row_ok) {
-        uint16_t* op = a.O + ((int64_t)my_row * a.Hq + h) * kHeadDim + 4 * hi;
+    // O goes through LDS so that it leaves in whole rows: a lane holds 8-byte pieces of one row, 16 of them spread
+    // over the 256 bytes; written to a wavefront-private 32 x 272-byte block (the K stages are free by now: the
+    // barrier above ended all tile reads) they come back as 16 lanes x 16 bytes per row, four rows per store.
+    {
+        unsigned char* blk = smem + kLdsK + wave * (32 * kKRow);
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -653,11 +657,21 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
                 uint2 w;
                 w.x = pack_bf16(oacc[db][4 * bb + 0] * inv, oacc[db][4 * bb + 1] * inv);
                 w.y = pack_bf16(oacc[db][4 * bb + 2] * inv, oacc[db][4 * bb + 3] * inv);
-                *(uint2*)(op + 32 * db + 8 * bb) = w;
+                *(uint2*)(blk + qi * kKRow + (32 * db + 8 * bb + 4 * hi) * 2) = w;
             }
-        if (hi == 0)
-            a.LSE[(int64_t)my_row * a.Hq + h] = ltot > 0.f ? (m_fin + __builtin_amdgcn_logf(ltot)) * kLn2 : -INFINITY;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");          // same wavefront wrote what it reads next
+        const int rows_here = min(32, q_hi - (q_lo + wave * 32));   // rows of this wavefront that exist (may be <= 0)
+        const int rsub = lane >> 4, c16 = lane & 15;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int r = 4 * i + rsub;
+            const uint4 w = *(const uint4*)(blk + r * kKRow + 16 * c16);
+            if (r < rows_here)
+                *(uint4*)(a.O + ((int64_t)(q_lo + wave * 32 + r) * a.Hq + h) * kHeadDim + 8 * c16) = w;
+        }
     }
+    if (row_ok && hi == 0)
+        a.LSE[(int64_t)my_row * a.Hq + h] = ltot > 0.f ? (m_fin + __builtin_amdgcn_logf(ltot)) * kLn2 : -INFINITY;
 }
 
 esp_status launch_prefill(const void* q, const void* k, const void* v, const int32_t* q_pos, const int32_t* kv_pos,
