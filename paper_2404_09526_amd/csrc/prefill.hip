@@ -58,6 +58,7 @@ struct PrefillArgs {
     const int32_t* q_pos; const int32_t* kv_pos; const int32_t* cu_q; const int32_t* cu_kv;
     uint16_t* O; float* LSE;
     int32_t batch, Tq, Tkv, Hq, Hkv, causal;
+    int32_t q_tiles, heads_per_xcd;   // upper bound of the number of query tiles; query heads per XCD (0: no split)
     float scale_log2;
 };
 
@@ -121,21 +122,8 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int G = a.Hq / a.Hkv;
 
-    // ---- which (query tile, head): XCD-aware (consecutive workgroup ids land on consecutive
-    //      XCDs, each with a private L2, so a KV head stays on one XCD), heaviest tiles first
-    int rank, h;
-    {
-        const int bid = blockIdx.x;
-        if (a.Hkv % 8 == 0) {
-            const int per = (a.Hkv / 8) * G;        // query heads per XCD
-            const int xcd = bid & 7, i = bid >> 3;
-            rank = i / per;
-            h = xcd * per + i % per;
-        } else {
-            rank = bid / a.Hq;
-            h = bid % a.Hq;
-        }
-    }
+    // ---- one query tile of one head (rank: position in the heaviest-first order of query tiles)
+    auto process = [&](const int rank, const int h) {
     const int kvh = h / G;
     int q_lo, q_hi, kv_lo, kv_hi;   // rows of this query tile; rows of its request in the shard
     {
@@ -672,6 +660,29 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     }
     if (row_ok && hi == 0)
         a.LSE[(int64_t)my_row * a.Hq + h] = ltot > 0.f ? (m_fin + __builtin_amdgcn_logf(ltot)) * kLn2 : -INFINITY;
+    };
+
+    // ---- persistent workgroups, one per CU, each working through a fixed list of (query tile, head) items.
+    //      Consecutive workgroup ids land on consecutive XCDs, each with a private L2, so XCD x keeps the heads
+    //      [x * per, (x + 1) * per) (all query heads of a KV head together).  Its items, ordered heaviest first
+    //      (later query tiles of a causal request see more keys), are dealt to its workgroups back and forth
+    //      (0 .. L-1, L-1 .. 0, ...): for the linear size profile of a causal sweep every workgroup gets the same
+    //      total.  Without the XCD split (head count not a multiple of 8) the same deal runs over all workgroups.
+    {
+        const int P = gridDim.x, p = blockIdx.x;
+        const bool split = a.heads_per_xcd > 0;
+        const int L = split ? P >> 3 : P, l = split ? p >> 3 : p;
+        const int width = split ? a.heads_per_xcd : a.Hq, h0 = split ? (p & 7) * a.heads_per_xcd : 0;
+        const int M = a.q_tiles * width;
+        bool first = true;
+        for (int s = 0; s * L < M; ++s) {
+            const int m = s * L + ((s & 1) ? L - 1 - l : l);
+            if (m >= M) continue;
+            if (!first) wg_barrier();       // every wavefront is done with the LDS of the previous item
+            first = false;
+            process(m / width, h0 + m % width);
+        }
+    }
 }
 
 esp_status launch_prefill(const void* q, const void* k, const void* v, const int32_t* q_pos, const int32_t* kv_pos,
@@ -686,9 +697,15 @@ esp_status launch_prefill(const void* q, const void* k, const void* v, const int
     a.O = (uint16_t*)O; a.LSE = LSE;
     a.batch = batch; a.Tq = Tq; a.Tkv = Tkv; a.Hq = Hq; a.Hkv = Hkv; a.causal = causal ? 1 : 0;
     a.scale_log2 = softmax_scale * kLog2e;
-    int64_t blocks = (int64_t)prefill_q_tiles_bound(Tq, batch) * Hq;
-    if (blocks > 0x7fffffff) return fail(ESP_ERR_INVALID_ARG, "prefill: too many tiles for one launch");
-    hipLaunchKernelGGL(prefill_kernel, dim3((unsigned)blocks), dim3(kPfWaves * 64), 0, stream, a);
+    a.q_tiles = prefill_q_tiles_bound(Tq, batch);
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        return fail(ESP_ERR_HIP, "prefill: cannot query the device");
+    const int64_t items = (int64_t)a.q_tiles * Hq;
+    // one workgroup per CU (a workgroup fills a CU's registers and LDS); fewer if there are fewer items
+    a.heads_per_xcd = (Hkv % 8 == 0 && cus % 8 == 0 && items >= cus) ? Hq / 8 : 0;
+    const unsigned grid = (unsigned)(items < cus ? items : cus);
+    hipLaunchKernelGGL(prefill_kernel, dim3(grid), dim3(kPfWaves * 64), 0, stream, a);
     return check_launch("prefill_kernel");
 }
 
