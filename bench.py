@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--retain", action="store_true",
                     help="proactive retention (scale-down during prefill): while each shard is attended, esp_kv_append keeps "
                          "ALL its rows in a token pool from a second stream; reports the overhead against prefill alone")
+    ap.add_argument("--fit-model", action="store_true",
+                    help="also time whole-request causal prefill batches of several length mixes, fit the iteration-time model "
+                         "(alpha + beta*sum(len) + gamma*sum(len^2)) with esp_fit_prefill_model and report its error")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy kernel (known traffic, to scale rocprofv3 --pmc byte counters)")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "bench_lwm7b_hbm_traffic.json"),
@@ -101,6 +104,45 @@ def cpu_baseline(pc, dc, wl, oracle):
         sample.append(f"decode: requests {reqs_s} x {len(heads)} heads ({tok} resident tokens)")
     out["sample"] = "; ".join(sample)
     return out
+
+
+MODEL_FIT_BATCHES = ([1024], [2048], [4096], [8192], [12288], [16384], [24576], [32768], [49152],
+                     [2048, 2048, 4096], [8192, 4096, 1024], [16384, 8192], [12288, 12288], [1024] * 8, [32768, 16384, 4096])
+
+
+def fit_model(esp, wl, torch, np, dev, batches=MODEL_FIT_BATCHES, Hq=32, Hkv=32, reps=5):
+    """Times one prefill call per batch of whole requests (causal self-attention, one shard holding every key),
+    fits the iteration-time model to the measurements and reports how well it reproduces them."""
+    s1, s2, ms = [], [], []
+    for bi, lens in enumerate(batches):
+        pc = wl.striped_prefill("fit", lens, 1, 0, Hq, Hkv, 100 + bi, dev)
+        sh = pc.shards[0]
+        ws = torch.empty(256, dtype=torch.uint8, device=dev)
+        O = torch.empty_like(pc.q); L = torch.empty((pc.Tq, pc.Hq), dtype=torch.float32, device=dev)
+        single = pc.batch == 1
+        run = lambda: esp.esp_partial_attn_prefill(pc.q, sh.k, sh.v, pc.q_pos, sh.kv_pos, None if single else pc.cu_q,
+                                                   None if single else sh.cu_kv, None if single else pc.max_q,
+                                                   None if single else sh.max_kv, softmax_scale=pc.scale, causal=True,
+                                                   O=O, LSE=L, workspace=ws)
+        run(); torch.cuda.synchronize()
+        best = float("inf")
+        for _ in range(3):                       # least of three averages: the short calls are noisy
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                run()
+            e1.record(); torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1) / reps)
+        ms.append(best)
+        s1.append(float(sum(lens))); s2.append(float(sum(x * x for x in lens)))
+        del pc, sh, O, L
+    t = np.array(ms) * 1e-3
+    coef = esp.esp_fit_prefill_model(s1, s2, t, weights=1.0 / t)     # relative residuals: the times span 500x
+    pred = coef[0] + coef[1] * np.array(s1) + coef[2] * np.array(s2)
+    rel = np.abs(pred - t) / t
+    return {"alpha_s": float(coef[0]), "beta_s_per_token": float(coef[1]), "gamma_s_per_token2": float(coef[2]),
+            "max_rel_err": float(rel.max()), "mean_rel_err": float(rel.mean()),
+            "samples": [{"lens": list(l), "ms": float(m), "model_ms": float(p * 1e3)} for l, m, p in zip(batches, ms, pred)]}
 
 
 def main():
@@ -221,6 +263,8 @@ def main():
                                      "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "traffic": None, "launch_ms": ms_decode,
                                      "bytes_per_launch": byts}
         result["config"].update({"decode_B": dc.B, "decode_total_tokens": dc.total_tokens, "pool_slots": dc.num_slots})
+    if args.fit_model:
+        result["model_fit"] = fit_model(esp, wl, torch, np, dev)
     if args.retain:
         # pool with room for every row of every shard, slots = seeded permutation (any token-level placement is legal)
         n_rows = sum(s.k.shape[0] for s in pc.shards)

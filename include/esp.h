@@ -9,6 +9,9 @@
  *                             this instance holds in its token-granular pool
  *   esp_merge_partials        log-sum-exp combination of partial results
  *   esp_kv_append             scatter of K/V rows into scheduler-chosen slots
+ * and, on the host, the scheduler's two numeric helpers for the prefill phase:
+ *   esp_plan_prefill_batches  batching plan (dynamic program over requests and instances)
+ *   esp_fit_prefill_model     least-squares fit of the iteration-time model
  *
  * Conventions common to all calls
  *   - Every data pointer is DEVICE memory owned by the caller unless a
@@ -139,6 +142,38 @@ esp_status esp_kv_append(
     const void* k, const void* v, const int32_t* slot_idx, int32_t T,
     void* k_pool, void* v_pool, int64_t num_slots, int32_t Hkv, int32_t D,
     void* stream);
+
+/*
+ * Prefill batching plan (Sec. 5.4 "Batching", the dynamic program over sorted requests and sorted elastic
+ * instances) -- host code, no GPU work; every pointer is HOST memory.
+ *
+ * Requests are given longest first (req_len[0] >= req_len[1] >= ... >= 1 tokens), instances in the scheduler's
+ * order with their unused key-value slots.  A plan cuts the requests and a prefix of the instances into the same
+ * number of consecutive non-empty pieces; batch b = requests [req_cuts[b-1], req_cuts[b]) on instances
+ * [inst_cuts[b-1], inst_cuts[b]) (cuts start at 0), and must fit: its tokens <= the unused slots of its instances.
+ * A batch costs sum over its requests of T / len, with T the iteration-time model below at the coefficients of
+ * its degree of parallelism d = its number of instances: coefs[3*(d-1) .. 3*(d-1)+2] = alpha, beta, gamma.
+ * The plan of least total cost is returned: *n_batches pieces, their end cuts in req_cuts / inst_cuts (room for
+ * min(n_req, n_inst) entries each), the cost in *cost.  If nothing fits, *n_batches = 0 and *cost = +inf.
+ * split_req / split_ins: NULL, or [(n_req+1) x (n_inst+1)] tables that receive, for the first i requests on the
+ * first k instances, where the last batch starts (the two monotone tables of the section; -1 = no plan).
+ */
+esp_status esp_plan_prefill_batches(
+    const int64_t* req_len, int32_t n_req, const int64_t* free_slots, int32_t n_inst,
+    const double* coefs, int32_t* req_cuts, int32_t* inst_cuts, int32_t* n_batches, double* cost,
+    int32_t* split_req, int32_t* split_ins);
+
+/*
+ * Iteration-time model of the prefill phase (Sec. 5.6 "Analytical model based on SIB"):
+ *   T(R) = alpha + beta * sum_{r in R} len_r + gamma * sum_{r in R} len_r^2,
+ * fitted by least squares to n >= 3 profiled batches (HOST arrays: per batch the two sums and the measured
+ * time).  weights: NULL, or n non-negative factors; sample i's equation is multiplied by weights[i] before the
+ * fit (1 / seconds[i] minimises the relative instead of the absolute residual).  coef receives alpha, beta,
+ * gamma; a column without information (all zero) gets coefficient 0.
+ */
+esp_status esp_fit_prefill_model(
+    const double* sum_len, const double* sum_len_sq, const double* seconds, const double* weights, int32_t n,
+    double* coef);
 
 /* Message of the last error on the calling thread (static storage, never NULL). */
 const char* esp_last_error(void);

@@ -16,7 +16,9 @@ Readings of the paper taken here (it leaves them open):
     with the coefficients of the batch's degree of parallelism (its number of instances);
   * batches take consecutive requests and consecutive instances, both from the front; instances left over at
     the end stay unused (the minimum over the second index in the text);
-  * D[j,i] <= V[l,k]: the tokens of the batch must fit the unused slots of its instances.
+  * D[j,i] <= V[l,k]: the tokens of the batch must fit the unused slots of its instances;
+  * "trained by the least square method" (Sec. 5.6) says nothing about weighting: the fit takes optional
+    per-sample weights; unweighted is the default.
 Pinning status: pinned by tests/test_plan_oracle_pins.py (hand-priced cases, closed forms, monotonicity in
 the resources, exact recovery of known coefficients).  The paper prints no numeric example for either.
 """
@@ -76,8 +78,14 @@ def brute_force_plan(req_len: Sequence[int], free_slots: Sequence[int],
     return best
 
 
-def fit_model(sum_len: Sequence[float], sum_len_sq: Sequence[float], times: Sequence[float]) -> np.ndarray:
-    """Least-squares (alpha, beta, gamma) of time ~ alpha + beta * sum_len + gamma * sum_len_sq."""
+def fit_model(sum_len: Sequence[float], sum_len_sq: Sequence[float], times: Sequence[float],
+              weights: Optional[Sequence[float]] = None) -> np.ndarray:
+    """Least-squares (alpha, beta, gamma) of time ~ alpha + beta * sum_len + gamma * sum_len_sq.  With weights,
+    sample i's equation is multiplied by weights[i] first (weights = 1 / time minimises the relative residual)."""
     A = np.stack([np.ones(len(times)), np.asarray(sum_len, np.float64), np.asarray(sum_len_sq, np.float64)], axis=1)
-    sol, *_ = np.linalg.lstsq(A, np.asarray(times, np.float64), rcond=None)
+    y = np.asarray(times, np.float64)
+    if weights is not None:
+        w = np.asarray(weights, np.float64)
+        A, y = A * w[:, None], y * w
+    sol, *_ = np.linalg.lstsq(A, y, rcond=None)
     return sol

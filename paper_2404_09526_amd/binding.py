@@ -21,6 +21,7 @@ ESP_MAX_PARTIALS = 16
 EXPORTS = (
     "esp_partial_attn_prefill", "esp_prefill_workspace_bytes", "esp_partial_attn_decode",
     "esp_decode_workspace_bytes", "esp_merge_partials", "esp_kv_append", "esp_last_error", "esp_version",
+    "esp_plan_prefill_batches", "esp_fit_prefill_model",
 )
 
 
@@ -49,6 +50,10 @@ def _load() -> ctypes.CDLL:
     L.esp_merge_partials.restype = i32
     L.esp_kv_append.argtypes = [vp, vp, vp, i32, vp, vp, i64, i32, i32, vp]
     L.esp_kv_append.restype = i32
+    L.esp_plan_prefill_batches.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp]
+    L.esp_plan_prefill_batches.restype = i32
+    L.esp_fit_prefill_model.argtypes = [vp, vp, vp, vp, i32, vp]
+    L.esp_fit_prefill_model.restype = i32
     L.esp_last_error.argtypes = []
     L.esp_last_error.restype = ctypes.c_char_p
     L.esp_version.argtypes = []
@@ -201,3 +206,44 @@ def esp_kv_append(k, v, slot_idx, k_pool, v_pool) -> None:
         raise ValueError("append: shape mismatch")
     _check(lib.esp_kv_append(_ptr(k), _ptr(v), _ptr(slot_idx), T, _ptr(k_pool), _ptr(v_pool), k_pool.shape[0], Hkv, D,
                              _stream()))
+
+
+def esp_plan_prefill_batches(req_len, free_slots, coefs, with_tables=False):
+    """Batching plan of the prefill phase (host code).  req_len: tokens per request, longest first; free_slots:
+    unused KV slots per instance; coefs: [n_inst][3] = (alpha, beta, gamma) at degree of parallelism 1..n_inst.
+    Returns (cost, req_cuts, inst_cuts) -- cost inf and empty cuts if nothing fits -- plus the two split tables
+    if with_tables."""
+    import numpy as np
+    rl = np.ascontiguousarray(req_len, dtype=np.int64); fs = np.ascontiguousarray(free_slots, dtype=np.int64)
+    cf = np.ascontiguousarray(coefs, dtype=np.float64)
+    n, m = rl.size, fs.size
+    if cf.shape != (m, 3):
+        raise ValueError("plan: coefs must be [n_inst][3]")
+    nb_max = max(1, min(n, m))
+    rc = np.zeros(nb_max, np.int32); ic = np.zeros(nb_max, np.int32)
+    nb = ctypes.c_int32(0); cost = ctypes.c_double(0.0)
+    sr = np.zeros((n + 1, m + 1), np.int32) if with_tables else None
+    si = np.zeros((n + 1, m + 1), np.int32) if with_tables else None
+    p = lambda arr: ctypes.c_void_p(arr.ctypes.data) if arr is not None else ctypes.c_void_p(0)
+    _check(lib.esp_plan_prefill_batches(p(rl), n, p(fs), m, p(cf), p(rc), p(ic), ctypes.addressof(nb),
+                                        ctypes.addressof(cost), p(sr), p(si)))
+    out = (cost.value, rc[:nb.value].tolist(), ic[:nb.value].tolist())
+    return out + (sr, si) if with_tables else out
+
+
+def esp_fit_prefill_model(sum_len, sum_len_sq, seconds, weights=None):
+    """Least-squares (alpha, beta, gamma) of seconds ~ alpha + beta * sum_len + gamma * sum_len_sq (host code);
+    weights: optional per-sample factors on the equations (1 / seconds: relative residual)."""
+    import numpy as np
+    a = np.ascontiguousarray(sum_len, dtype=np.float64); b = np.ascontiguousarray(sum_len_sq, dtype=np.float64)
+    t = np.ascontiguousarray(seconds, dtype=np.float64)
+    if not (a.size == b.size == t.size):
+        raise ValueError("fit: arrays differ in length")
+    w = None if weights is None else np.ascontiguousarray(weights, dtype=np.float64)
+    if w is not None and w.size != t.size:
+        raise ValueError("fit: weights differ in length")
+    out = np.zeros(3, np.float64)
+    _check(lib.esp_fit_prefill_model(ctypes.c_void_p(a.ctypes.data), ctypes.c_void_p(b.ctypes.data),
+                                     ctypes.c_void_p(t.ctypes.data), ctypes.c_void_p(w.ctypes.data if w is not None else 0),
+                                     a.size, ctypes.c_void_p(out.ctypes.data)))
+    return out

@@ -152,3 +152,4 @@ def test_config5_decode_pool_16M_slots_gqa(esp, cuda):
     sample = pick_requests(lens, 10)
     dc = wl.config5_decode(cuda, sample_reqs=sample)
     check_decode_sampled(esp, dc, sample, heads_per_req=np.array([0, 5, 10, 15, 17, 22, 27, 28, 31], np.int64))
+

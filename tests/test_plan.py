@@ -1,0 +1,112 @@
+"""The host-side planning calls of libesp (no GPU needed) against oracle/plan.py: the dynamic program of
+Sec. 5.4 must find the cost the exhaustive enumeration finds, with a plan that is valid and prices to that cost;
+the fit of Sec. 5.6 must agree with the library least-squares routine."""
+import numpy as np
+import pytest
+
+from oracle import plan as oplan
+from paper_2404_09526_amd import binding as esp
+
+
+def random_instance(rng, n_max=6, m_max=4):
+    n, m = int(rng.integers(1, n_max + 1)), int(rng.integers(1, m_max + 1))
+    lens = sorted((int(x) for x in rng.integers(1, 4000, n)), reverse=True)
+    slots = [int(x) for x in rng.integers(0, 6000, m)]
+    # per degree of parallelism: overhead grows a little, the quadratic and linear terms shrink less than 1/d
+    coefs = [(float(rng.uniform(1e-4, 1e-3)) * (1 + 0.2 * d), float(rng.uniform(1e-7, 1e-6)) / d ** 0.9,
+              float(rng.uniform(1e-10, 1e-9)) / d ** 0.8) for d in range(1, m + 1)]
+    return lens, slots, coefs
+
+
+def test_dp_matches_exhaustive_enumeration():
+    rng = np.random.default_rng(2024)
+    feasible = infeasible = multi = 0
+    for _ in range(300):
+        lens, slots, coefs = random_instance(rng)
+        want, _, _ = oplan.brute_force_plan(lens, slots, coefs)
+        cost, rc, ic = esp.esp_plan_prefill_batches(lens, slots, coefs)
+        if want is None:
+            assert cost == float("inf") and rc == [] and ic == []
+            infeasible += 1
+            continue
+        feasible += 1
+        multi += len(rc) > 1
+        assert cost == pytest.approx(want, rel=1e-12)
+        # the plan itself: well-formed, fits, and prices (by the oracle) to the reported cost
+        assert len(rc) == len(ic) >= 1 and rc[-1] == len(lens) and ic[-1] <= len(slots)
+        assert all(b > a for a, b in zip([0] + rc[:-1], rc)) and all(b > a for a, b in zip([0] + ic[:-1], ic))
+        assert oplan.plan_cost(lens, slots, coefs, rc, ic) == pytest.approx(cost, rel=1e-12)
+    assert feasible > 100 and infeasible > 10 and multi > 30      # the cases exercise all three outcomes
+
+
+def test_dp_hand_priced_cases():
+    coefs = [(0.0, 0.0, 1.0), (0.0, 0.0, 0.5)]
+    assert esp.esp_plan_prefill_batches([8, 2], [100, 100], coefs) == (pytest.approx(10.0), [1, 2], [1, 2])
+    assert esp.esp_plan_prefill_batches([8, 2], [5, 5], coefs) == (pytest.approx(21.25), [2], [2])
+    assert esp.esp_plan_prefill_batches([8, 4], [5, 5], coefs)[0] == float("inf")
+
+
+def test_split_tables_and_the_monotonicity_the_section_states():
+    """The call can return the two tables of last split points.  The section states that they move monotonically
+    with the instance count and the request count (and that this could cut the search); under the reading taken
+    here that does not hold in general, which is why the call searches every split: with perfectly linear speed-up,
+    lengths (9, 7) and time = 2 * sum(len^2) / d, two instances are best used one request each (32 against 33.02
+    together), three instances best all together (22.01 against 23 and 25), so the request split point goes from 1
+    back to 0.  The tables must show exactly that, and agree with the enumeration at every (i, k)."""
+    lens, coefs = [9, 7], [(0.0, 0.0, 2.0 / d) for d in (1, 2, 3)]
+    cost, rc, ic, sr, si = esp.esp_plan_prefill_batches(lens, [10 ** 9] * 3, coefs, with_tables=True)
+    assert cost == pytest.approx(2 * 130 / 3 * (1 / 9 + 1 / 7)) and rc == [2] and ic == [3]
+    assert sr[2, 2] == 1 and si[2, 2] == 1 and sr[2, 3] == 0 and si[2, 3] == 0
+    # every table entry is the start of the last batch of an optimal plan for that prefix: re-price by enumeration
+    rng = np.random.default_rng(7)
+    for _ in range(40):
+        lens, slots, coefs = random_instance(rng, 5, 4)
+        _, _, _, sr, si = esp.esp_plan_prefill_batches(lens, slots, coefs, with_tables=True)
+        for i in range(1, len(lens) + 1):
+            for k in range(1, len(slots) + 1):
+                best = None
+                for parts in range(1, min(i, k) + 1):           # all k instances in use, as f[i][k] is defined
+                    for rcut in oplan._compositions(i, parts):
+                        for icut in oplan._compositions(k, parts):
+                            c = oplan.plan_cost(lens[:i], slots[:k], coefs[:k], rcut, icut)
+                            if c is not None and (best is None or c < best[0] - 1e-15):
+                                best = (c, rcut, icut)
+                if best is None:
+                    assert sr[i, k] == -1 and si[i, k] == -1
+                else:
+                    j, l = int(sr[i, k]), int(si[i, k])
+                    assert 0 <= j < i and 0 <= l < k
+                    last = oplan.batch_cost(lens[j:i], coefs[k - l - 1])
+                    assert sum(lens[j:i]) <= sum(slots[l:k])
+                    # cost of the best plan = cost of the best plan of the prefix (j, l) + the last batch
+                    if j == 0:
+                        assert l == 0 and last == pytest.approx(best[0], rel=1e-12)
+
+
+def test_plan_argument_errors():
+    coefs = [(0.0, 0.0, 1.0)]
+    with pytest.raises(esp.EspError):
+        esp.esp_plan_prefill_batches([2, 8], [100], coefs)        # not sorted longest first
+    with pytest.raises(esp.EspError):
+        esp.esp_plan_prefill_batches([0], [100], coefs)           # empty request
+    with pytest.raises(esp.EspError):
+        esp.esp_plan_prefill_batches([4], [-1], coefs)
+
+
+def test_fit_matches_library_least_squares():
+    rng = np.random.default_rng(3)
+    for _ in range(20):
+        k = int(rng.integers(3, 30))
+        lens = [rng.integers(256, 65536, int(rng.integers(1, 5))).astype(np.float64) for _ in range(k)]
+        s1 = np.array([x.sum() for x in lens]); s2 = np.array([(x * x).sum() for x in lens])
+        t = 4e-5 + 3e-9 * s1 + 5e-13 * s2
+        t = t * (1 + 0.02 * rng.standard_normal(k))                       # 2 % measurement noise
+        got = esp.esp_fit_prefill_model(s1, s2, t)
+        want = oplan.fit_model(s1, s2, t)
+        assert got == pytest.approx(want, rel=1e-6, abs=1e-18)
+        got = esp.esp_fit_prefill_model(s1, s2, t, weights=1.0 / t)
+        want = oplan.fit_model(s1, s2, t, weights=1.0 / t)
+        assert got == pytest.approx(want, rel=1e-6, abs=1e-18)
+    assert esp.esp_fit_prefill_model([0.0, 1.0, 2.0], [0.0, 0.0, 0.0], [1.0, 3.0, 5.0]) == pytest.approx([1.0, 2.0, 0.0])
+    with pytest.raises(esp.EspError):
+        esp.esp_fit_prefill_model([1.0, 2.0], [1.0, 4.0], [1.0, 2.0])

@@ -81,3 +81,17 @@ def test_fit_recovers_known_coefficients_and_a_textbook_line():
     # degenerate to ordinary linear regression when the quadratic column is zero: y = 1 + 2x through 3 exact points
     sol = plan.fit_model([0.0, 1.0, 2.0], [0.0, 0.0, 0.0], [1.0, 3.0, 5.0])
     assert sol[0] == pytest.approx(1.0) and sol[1] == pytest.approx(2.0)
+
+
+def test_weighted_fit_reduces_to_textbook_cases():
+    # weights (1, 1, 0): the third sample is ignored -> the line through the first two points exactly
+    sol = plan.fit_model([0.0, 1.0, 5.0], [0.0, 0.0, 0.0], [1.0, 3.0, 100.0], weights=[1.0, 1.0, 0.0])
+    assert sol[0] == pytest.approx(1.0) and sol[1] == pytest.approx(2.0)
+    # equal weights change nothing
+    rng = np.random.default_rng(2)
+    x = rng.uniform(1, 9, 7); t = 1 + 2 * x + 0.5 * x * x + 0.01 * rng.standard_normal(7)
+    assert plan.fit_model(x, x * x, t, weights=[3.0] * 7) == pytest.approx(plan.fit_model(x, x * x, t), rel=1e-9)
+    # constant model, weights 1/t: minimising sum((a - t_i)^2 / t_i^2) gives a = sum(1/t) / sum(1/t^2)
+    t = np.array([1.0, 2.0, 4.0])
+    sol = plan.fit_model([0.0] * 3, [0.0] * 3, t, weights=1 / t)
+    assert sol[0] == pytest.approx((1 / t).sum() / (1 / t ** 2).sum())
