@@ -4,9 +4,10 @@
 // in Sec. 6).  Emits the un-merged output, normalised within the shard, and its log-sum-exp.
 //
 // Mapping to gfx950 (64-wide wavefronts, MFMA 32x32x16 bf16, 160 KiB LDS):
-//   * a workgroup of 8 wavefronts owns 256 query rows of one head; each wavefront owns 32 rows
-//     and keeps their Q fragment (B operand), the softmax state and the fp32 output accumulator
-//     in registers for the whole KV sweep;
+//   * one persistent workgroup of 8 wavefronts per CU works through a fixed list of items; an
+//     item is 256 query rows of one head: each wavefront owns 32 rows and keeps their Q fragment
+//     (B operand), the softmax state and the fp32 output accumulator in registers for the whole
+//     KV sweep;
 //   * K/V tiles of 64 rows are fetched straight from global memory into a 4-stage LDS ring
 //     (global_load ... lds, no register staging), K four tiles and V two tiles ahead of their use;
 //   * the K tile is the A operand of S^T = K Q^T, so a lane ends up with scores of ONE query
