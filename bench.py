@@ -145,6 +145,11 @@ def fit_model(esp, wl, torch, np, dev, batches=MODEL_FIT_BATCHES, Hq=32, Hkv=32,
             "samples": [{"lens": list(l), "ms": float(m), "model_ms": float(p * 1e3)} for l, m, p in zip(batches, ms, pred)]}
 
 
+def note(msg):
+    """Progress line on stderr (stdout carries only the JSON line)."""
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -158,6 +163,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     pc = dc = None
+    note("generating the synthetic inputs of workload '%s'" % args.workload)
     if args.workload == "lwm7b":
         pc = wl.config2_prefill(dev)
         lens = wl.lognormal_lengths(64, 8192, 1024, 131072, 2)
@@ -221,6 +227,7 @@ def main():
         dst.copy_(src)                      # 1 GiB read + 1 GiB written by one elementwise kernel
         torch.cuda.synchronize()
         del src, dst
+    note("inputs ready; %d warm-up and %d timed steps" % (args.warmup, args.steps))
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -311,7 +318,9 @@ def main():
             result["roofline_decode"]["traffic"] = tr.get("decode_partial_kernel")
     if not args.no_cpu_baseline:
         import oracle
+        note("timing the CPU oracle on a bounded sample (10-30 s)")
         result["cpu_baseline"] = cpu_baseline(pc, dc, wl, oracle)
+        note("done")
     print(json.dumps(result), flush=True)
 
 
