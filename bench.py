@@ -54,7 +54,10 @@ def cpu_baseline(pc, dc, wl, oracle):
     sample = []
     if pc is not None:
         rng = np.random.default_rng(0)
-        n = 98304                               # about 10 s of fp64 work on 16 cores
+        # about 10 s of fp64 work on 16 cores = 4e8 visible (query, key) pairs: 98304 (row, head) pairs on the
+        # default workload, fewer where a row sees more keys
+        pairs_per_row = max(1.0, pc.visible_pairs_per_head / len(pc.shards) / max(pc.Tq, 1))
+        n = int(min(98304, max(256, 4.0e8 / pairs_per_row)))
         rows = rng.integers(0, pc.Tq, n).astype(np.int64)
         heads = rng.integers(0, pc.Hq, n).astype(np.int64)
         cu_q = wl.host_i32(pc.cu_q)
