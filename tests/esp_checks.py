@@ -4,19 +4,22 @@ Tolerances (bf16 output, fp32 accumulation):
   O    |dO| <= 1e-2 * max(1, |O_ref|) element-wise: max-abs 1e-2 wherever |O_ref| <= 1; above that the bf16
        output format alone rounds by up to 2^-9 * |O| (0.0156 at |O| = 4, reached by rows that see only a
        few N(0,1) value rows), so the bound scales with the magnitude.  AND per (row, head)
-       max|dO| <= 2^-7 * max|O_ref| + 1e-5 and cosine >= 0.999 (these keep the test meaningful for long
-       KV, where |O| ~ 1/sqrt(n) is tiny and an all-zero output would pass the absolute bound);
+       max|dO| <= (1 + r) * 2^-8 * max|O_ref| + 1e-5 and cosine >= 0.999 (these keep the test meaningful for
+       long KV, where |O| ~ 1/sqrt(n) is tiny and an all-zero output would pass the absolute bound), with r the
+       number of bf16 roundings between the fp32 arithmetic and the compared value: 1 for a kernel's own output
+       (2^-8 for that rounding, another 2^-8 for the bf16 probabilities of the second product), 2 for a merge
+       of bf16 partials (each partial was rounded once already);
   LSE  |dLSE| <= 1e-4 * max(1, |LSE_ref|), and -inf must match exactly.
 """
 import numpy as np
 
 O_ABS_TOL = 1e-2
-O_REL_TOL = 2.0 ** -7
+O_REL_UNIT = 2.0 ** -8
 LSE_REL_TOL = 1e-4
 
 
-def check_o_lse(O_gpu, LSE_gpu, O_ref, LSE_ref, what=""):
-    """O_* [n, D], LSE_* [n]; gpu values as float64 arrays."""
+def check_o_lse(O_gpu, LSE_gpu, O_ref, LSE_ref, what="", roundings=1):
+    """O_* [n, D], LSE_* [n]; gpu values as float64 arrays; roundings: see the module docstring."""
     O_gpu = np.asarray(O_gpu, np.float64); LSE_gpu = np.asarray(LSE_gpu, np.float64)
     assert O_gpu.shape == O_ref.shape and LSE_gpu.shape == LSE_ref.shape, what
     assert not np.isnan(O_gpu).any() and not np.isnan(LSE_gpu).any(), f"{what}: NaN in GPU output"
@@ -35,7 +38,7 @@ def check_o_lse(O_gpu, LSE_gpu, O_ref, LSE_ref, what=""):
     assert worst <= O_ABS_TOL, f"{what}: O error {worst:.3e} (in units of max(1, |O_ref|)); max-abs {o_abs:.3e}"
     row_ref = np.abs(O_ref[fin]).max(axis=1)
     row_err = dO.max(axis=1)
-    bad = row_err > O_REL_TOL * row_ref + 1e-5
+    bad = row_err > (1 + roundings) * O_REL_UNIT * row_ref + 1e-5
     assert not bad.any(), f"{what}: relative O error, worst {np.max(row_err / (row_ref + 1e-30)):.3e}"
     num = (O_gpu[fin] * O_ref[fin]).sum(1)
     den = np.linalg.norm(O_gpu[fin], axis=1) * np.linalg.norm(O_ref[fin], axis=1)

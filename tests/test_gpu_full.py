@@ -63,7 +63,7 @@ def check_prefill_sampled(esp, pc, n_random_per_req, seed):
         torch.cuda.synchronize()
         Oref, Lref = oracle.merge_partials(np.stack([r[0] for r in refs]), np.stack([r[1] for r in refs]))
         ri, hi = torch.from_numpy(rows).to(Om.device), torch.from_numpy(heads).to(Om.device)
-        st = check_o_lse(Om[ri, hi].float().cpu().numpy(), Lm[ri, hi].cpu().numpy(), Oref, Lref, f"{pc.name} merged")
+        st = check_o_lse(Om[ri, hi].float().cpu().numpy(), Lm[ri, hi].cpu().numpy(), Oref, Lref, f"{pc.name} merged", roundings=2)
         say(f"  merged ok: {st}")
         # causal striped layout with r_q = 0: every row sees at least its own token in shard 0
         assert torch.isfinite(Lm).all()
