@@ -317,3 +317,29 @@ def test_prefill_more_items_than_workgroups(esp, cuda, Hq, Hkv):
     pc = wl.contiguous_prefill(f"many-items-{Hq}/{Hkv}", Tq, 200, [(0, 330), (330, 700)], Hq, Hkv, 51, cuda)
     pc.q_pos[:] = torch.randint(0, 900, (Tq,), dtype=torch.int32, device=cuda)       # every tile sees a different part
     run_prefill_case(esp, pc)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("seed", list(range(10)))
+def test_prefill_randomized_layouts(esp, cuda, seed):
+    """Seeded random layouts: head counts, batch, ragged lengths up to several query tiles and a dozen KV tiles,
+    striped shards with a random stripe offset, sometimes shuffled positions or no mask.  Every row is checked."""
+    rng = np.random.default_rng(1000 + seed)
+    Hq, Hkv = [(4, 4), (8, 2), (4, 1), (16, 8), (32, 8), (8, 8)][int(rng.integers(0, 6))]
+    n_req = int(rng.integers(1, 5))
+    chunks = [int(rng.integers(1, 900)) for _ in range(n_req)]
+    n_shards = int(rng.integers(1, 4))
+    pc = wl.striped_prefill(f"rand{seed}-{Hq}/{Hkv}", chunks, n_shards, int(rng.integers(0, n_shards)), Hq, Hkv, 2000 + seed, cuda)
+    mode = int(rng.integers(0, 4))
+    if mode == 1:                                   # positions shuffled inside every request (rows keep their data)
+        g = torch.Generator(device="cpu").manual_seed(seed)
+        cu = wl.host_i32(pc.cu_q)
+        for t in [pc] + pc.shards:
+            pos = t.q_pos if t is pc else t.kv_pos
+            for r in range(n_req):
+                lo, hi = int(cu[r]), int(cu[r + 1])
+                pos[lo:hi] = pos[lo:hi][torch.randperm(hi - lo, generator=g).to(cuda)]
+    elif mode == 2:
+        pc.causal = False
+    say(f"layout: chunks={chunks} shards={n_shards} mode={mode}")
+    run_prefill_case(esp, pc)
