@@ -111,7 +111,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     // each array's base folded into the per-lane register every operand read of the loop needs no address math.
     constexpr int kLdsV = 0, kLdsK = kLdsV + kStages * kTileBytes, kLdsPos = kLdsK + kStages * kKTileBytes,
                   kLdsQmm = kLdsPos + kStages * kBN * 4, kLdsSched = kLdsQmm + 2 * kPfWaves * 4,
-                  kLdsFlag = kLdsSched + kPfWaves * (1 + kPfWaves) * 4, kLdsTotal = kLdsFlag + 16;
+                  kLdsFlag = kLdsSched + kPfWaves * (1 + 2 * kPfWaves) * 4, kLdsTotal = kLdsFlag + 16;
     __shared__ __attribute__((aligned(1024))) unsigned char smem[kLdsTotal];
     unsigned char (*lds_k)[kKTileBytes] = (unsigned char (*)[kKTileBytes])(smem + kLdsK);
     unsigned char (*lds_v)[kTileBytes] = (unsigned char (*)[kTileBytes])(smem + kLdsV);
@@ -289,20 +289,21 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     // ---- tile schedule of this workgroup: n_vis = 1 + last tile some row can see (tiles before it that are
     //      hidden, possible only with unordered positions, are swept fully masked); first_mask = first tile
     //      this wavefront has to mask (every later tile is masked too, which is exact for ascending positions
-    //      and merely redundant otherwise)
-    int n_vis = nkt, first_mask = nkt;
+    //      and merely redundant otherwise); n_need = 1 + last tile a row of this wavefront can see: beyond it
+    //      the wavefront only keeps up its share of the transfers and the barriers
+    int n_vis = nkt, first_mask = nkt, n_need = nkt;
     if (a.causal) {
         int wg_qmax = lds_qmm[1][0];
 #pragma unroll
         for (int w = 1; w < kPfWaves; ++w) wg_qmax = max(wg_qmax, lds_qmm[1][w]);
-        int qmin_w[kPfWaves];
+        int qmin_w[kPfWaves], qmax_w[kPfWaves];
 #pragma unroll
-        for (int w = 0; w < kPfWaves; ++w) qmin_w[w] = lds_qmm[0][w];
+        for (int w = 0; w < kPfWaves; ++w) { qmin_w[w] = lds_qmm[0][w]; qmax_w[w] = lds_qmm[1][w]; }
         // every thread looks at tiles tid, tid + 512, ...; wavefront-wide ballots turn the per-tile tests into bit
         // masks, whose highest / lowest set bit gives this wavefront's candidates (no atomics on shared words)
-        int last_vis = -1, fm[kPfWaves];
+        int last_vis = -1, fm[kPfWaves], lw[kPfWaves];
 #pragma unroll
-        for (int w = 0; w < kPfWaves; ++w) fm[w] = nkt;
+        for (int w = 0; w < kPfWaves; ++w) { fm[w] = nkt; lw[w] = -1; }
         for (int t0 = wave * 64; t0 < nkt; t0 += kPfWaves * 64) {
             const int2 mm = t0 == wave * 64 ? mm_first : tile_bounds(t0 + lane);
             const uint64_t vis = __builtin_amdgcn_ballot_w64(mm.x <= wg_qmax);
@@ -311,24 +312,28 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
             for (int w = 0; w < kPfWaves; ++w) {
                 const uint64_t mk = __builtin_amdgcn_ballot_w64(mm.y > qmin_w[w]);
                 if (mk && fm[w] == nkt) fm[w] = t0 + __builtin_ctzll(mk);
+                const uint64_t vw = __builtin_amdgcn_ballot_w64(mm.x <= qmax_w[w]);
+                if (vw) lw[w] = t0 + 63 - __builtin_clzll(vw);
             }
         }
         // candidates of wavefront `wave` -> LDS (one row per scanning wavefront), then everyone combines the rows
-        int32_t (*cand)[1 + kPfWaves] = (int32_t (*)[1 + kPfWaves])(smem + kLdsSched);
+        int32_t (*cand)[1 + 2 * kPfWaves] = (int32_t (*)[1 + 2 * kPfWaves])(smem + kLdsSched);
         if (lane == 0) {
             cand[wave][0] = last_vis;
 #pragma unroll
-            for (int w = 0; w < kPfWaves; ++w) cand[wave][1 + w] = fm[w];
+            for (int w = 0; w < kPfWaves; ++w) { cand[wave][1 + w] = fm[w]; cand[wave][1 + kPfWaves + w] = lw[w]; }
         }
         wg_barrier();
-        int lv = -1, fmk = nkt;
+        int lv = -1, fmk = nkt, lwk = -1;
 #pragma unroll
         for (int sw = 0; sw < kPfWaves; ++sw) {
             lv = max(lv, cand[sw][0]);
             fmk = min(fmk, cand[sw][1 + wave]);
+            lwk = max(lwk, cand[sw][1 + kPfWaves + wave]);
         }
         n_vis = __builtin_amdgcn_readfirstlane(lv) + 1;
         first_mask = __builtin_amdgcn_readfirstlane(fmk);
+        n_need = __builtin_amdgcn_readfirstlane(lwk) + 1;     // 1 + last tile a row of THIS wavefront can see
     }
 
     // ---- operand read offsets
@@ -521,7 +526,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     wait_vm<0>();
     if (ragged_tile >= 0 && ragged_tile < 2) seal_tail(ragged_tile);
     wg_barrier();
-    if (n_vis > 0) {
+    if (n_need > 0) {
         read_k(0, 0, 0);
         read_k(1, 0, 1);
 #pragma unroll
@@ -549,7 +554,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     //      stream has no conditional code at all (a wavefront may leave this part earlier than its neighbours:
     //      the barriers and transfers per iteration are the same in both kinds);
     //   2. general iterations for the rest, again in groups of four, then one by one.
-    const int n_plain = max(0, min(min(n_vis - 4, mask_from), ragged_tile >= 0 ? nkt - 5 : INT_MAX)) & ~3;
+    const int n_plain = max(0, min(min(min(n_vis - 4, n_need), mask_from), ragged_tile >= 0 ? nkt - 5 : INT_MAX)) & ~3;
     int j = 0;
     for (; j < n_plain; j += 4) {
         iteration(IC<0>{}, IC<0>{}, IC<1>{}, j);
@@ -557,26 +562,42 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         iteration(IC<2>{}, IC<0>{}, IC<1>{}, j + 2);
         iteration(IC<3>{}, IC<1>{}, IC<1>{}, j + 3);
     }
-    for (; j + 4 <= n_vis; j += 4) {
+    for (; j + 4 <= n_need; j += 4) {
         iteration(IC<0>{}, IC<0>{}, IC<0>{}, j);
         iteration(IC<1>{}, IC<1>{}, IC<0>{}, j + 1);
         iteration(IC<2>{}, IC<0>{}, IC<0>{}, j + 2);
         iteration(IC<3>{}, IC<1>{}, IC<0>{}, j + 3);
     }
-    if (j < n_vis) {
+    if (j < n_need) {
         iteration(IC<0>{}, IC<0>{}, IC<0>{}, j);
-        if (j + 1 < n_vis) {
+        if (j + 1 < n_need) {
             iteration(IC<1>{}, IC<1>{}, IC<0>{}, j + 1);
-            if (j + 2 < n_vis) iteration(IC<2>{}, IC<0>{}, IC<0>{}, j + 2);
+            if (j + 2 < n_need) iteration(IC<2>{}, IC<0>{}, IC<0>{}, j + 2);
         }
     }
-    if (n_vis > 0) {                                                // last chunk of the last tile
-        const uint32_t last_off = (uint32_t)((n_vis - 1) & 3) * kTileBytes;
+    if (n_need > 0) {                                               // last chunk of this wavefront's last tile
+        const uint32_t last_off = (uint32_t)((n_need - 1) & 3) * kTileBytes;
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
             oacc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frv[m & 1].v, pf[1][1].v, oacc[m], 0, 0, 0);
             if (m < 2) read_v(m & 1, last_off, 14 + m);
         }
+    }
+    //   3. tiles that only other wavefronts can see: no arithmetic, but the same transfers, waits and barrier as
+    //      in every other iteration (stages computed at run time here)
+    for (int jj = n_need; jj < n_vis; ++jj) {
+        const bool do_k = jj < n_vis - 4, do_v = jj < n_vis - 2;
+        const bool tail_k = jj + 4 == ragged_tile, tail_v = jj + 2 == ragged_tile;
+        if (do_k) fetch_k_part(k_next, jj & 3, tail_k, 2);
+        if (do_v) fetch_v_part(v_next, p_next, (jj + 2) & 3, tail_v, 2);
+        if (do_k) { fetch_k_part(k_next, jj & 3, tail_k, 0); fetch_k_part(k_next, jj & 3, tail_k, 1); }
+        if (do_v) { fetch_v_part(v_next, p_next, (jj + 2) & 3, tail_v, 0); fetch_v_part(v_next, p_next, (jj + 2) & 3, tail_v, 1); }
+        k_next += tile_bytes; v_next += tile_bytes; p_next += kBN;
+        if (do_k) wait_vm<4>();
+        else if (do_v) wait_vm<2>();
+        else wait_vm<0>();
+        if (__builtin_expect(jj + 1 == ragged_tile, 0)) seal_tail((jj + 1) & 3);
+        asm volatile("s_barrier" ::: "memory");
     }
 
     // ---- the plain sweep, for a workgroup whose optimistic pass met scores outside its range: one tile at a
