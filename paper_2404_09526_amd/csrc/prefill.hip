@@ -47,8 +47,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4_t;
 
 static int32_t prefill_q_tiles_bound(int32_t Tq, int32_t batch) { return Tq / kBM + batch; }
 
-// The prefill path keeps nothing in global scratch memory any more; a minimal block stays reserved so that
-// callers written against the workspace contract keep working.
+// Global scratch memory of the prefill path: one item counter (the first word of the block).
 size_t prefill_workspace_bytes(int32_t Tq, int32_t Tkv, int32_t batch, int32_t Hq, int32_t Hkv) {
     (void)Tq; (void)Tkv; (void)batch; (void)Hq; (void)Hkv;
     return 256;
@@ -60,6 +59,7 @@ struct PrefillArgs {
     uint16_t* O; float* LSE;
     int32_t batch, Tq, Tkv, Hq, Hkv, causal;
     int32_t q_tiles, heads_per_xcd;   // upper bound of the number of query tiles; query heads per XCD (0: no split)
+    int32_t* queue;                   // counter of the item pool, zero at launch
     float scale_log2;
 };
 
@@ -123,8 +123,12 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int G = a.Hq / a.Hkv;
 
-    // ---- one query tile of one head (rank: position in the heaviest-first order of query tiles)
-    auto process = [&](const int rank, const int h) {
+    // ---- one query tile of one head (rank: position in the heaviest-first order of query tiles).  Returns false
+    //      if there is no such tile.  With `claim_from` set, thread 0 also draws the workgroup's next item from that
+    //      counter (a device-wide atomic, issued when the sweep is done; its latency hides behind the epilogue) and
+    //      leaves the counter's old value in LDS (lds_next), to be read after the next workgroup barrier.
+    int32_t* lds_next = (int32_t*)(smem + kLdsFlag + 4);
+    auto process = [&](const int rank, const int h, int32_t* claim_from) {
     const int kvh = h / G;
     int q_lo, q_hi, kv_lo, kv_hi;   // rows of this query tile; rows of its request in the shard
     {
@@ -133,7 +137,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
             int len = a.cu_q ? a.cu_q[r + 1] - a.cu_q[r] : a.Tq;
             total += (len + kBM - 1) / kBM;
         }
-        if (rank >= total) return;
+        if (rank >= total) return false;
         int tl = total - 1 - rank;   // later tiles of a causal request see more keys: run them first
         int r = 0;
         for (;; ++r) {
@@ -524,6 +528,9 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
 
     // ---- prologue: K(0..3), V(0), V(1) were requested at kernel entry; S^T of tile 0, first fragments
     wait_vm<0>();
+    // the Q fragments have landed with everything else; said in a way the compiler's own bookkeeping of loads
+    // in flight understands, or every later reuse of these registers makes it wait for "pending" loads
+    asm volatile("" :: "v"(qf[0]), "v"(qf[1]), "v"(qf[2]), "v"(qf[3]), "v"(qf[4]), "v"(qf[5]), "v"(qf[6]), "v"(qf[7]));
     if (ragged_tile >= 0 && ragged_tile < 2) seal_tail(ragged_tile);
     wg_barrier();
     if (n_need > 0) {
@@ -604,6 +611,16 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     //      time through stage 0, row maximum before the exponentials, nothing overlapped.  Slow and exact.
     float m_fin = m_use;
     wg_barrier();                                                   // everyone's flag write and last LDS reads are done
+    // the draw of the next item: as late as possible, so that items go out in the order in which workgroups
+    // really become free, and early enough for the answer to arrive while the results are written
+    int next_item = 0;
+    if (claim_from && tid == 0) {
+        // an index the compiler cannot see through: with a provably uniform address it rewrites the atomic into
+        // its one-per-wavefront form, which needs the answer at once instead of after the epilogue
+        int idx = 0;
+        asm volatile("" : "+v"(idx));
+        next_item = __hip_atomic_fetch_add(claim_from + idx, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     if (__builtin_amdgcn_readfirstlane(*lds_unsafe) != 0) {
         float m_ref = -INFINITY;
         lsum = 0.f;
@@ -672,47 +689,81 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");          // same wavefront wrote what it reads next
         const int rows_here = min(32, q_hi - (q_lo + wave * 32));   // rows of this wavefront that exist (may be <= 0)
         const int rsub = lane >> 4, c16 = lane & 15;
+        uint16_t* orow = a.O + ((int64_t)(q_lo + wave * 32 + rsub) * a.Hq + h) * kHeadDim + 8 * c16;
+        const int64_t ostep = (int64_t)4 * a.Hq * kHeadDim;
+        if (rows_here >= 32) {                                      // all rows exist: eight stores in a row, no branches
+            uint4 w[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int r = 4 * i + rsub;
-            const uint4 w = *(const uint4*)(blk + r * kKRow + 16 * c16);
-            if (r < rows_here)
-                *(uint4*)(a.O + ((int64_t)(q_lo + wave * 32 + r) * a.Hq + h) * kHeadDim + 8 * c16) = w;
+            for (int i = 0; i < 8; ++i) w[i] = *(const uint4*)(blk + (4 * i + rsub) * kKRow + 16 * c16);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) *(uint4*)(orow + i * ostep) = w[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int r = 4 * i + rsub;
+                const uint4 w = *(const uint4*)(blk + r * kKRow + 16 * c16);
+                if (r < rows_here) *(uint4*)(orow + i * ostep) = w;
+            }
         }
     }
     if (row_ok && hi == 0)
         a.LSE[(int64_t)my_row * a.Hq + h] = ltot > 0.f ? (m_fin + __builtin_amdgcn_logf(ltot)) * kLn2 : -INFINITY;
+    if (claim_from && tid == 0) *lds_next = next_item;
+    return true;
     };
 
-    // ---- persistent workgroups, one per CU, each working through a fixed list of (query tile, head) items.
-    //      Consecutive workgroup ids land on consecutive XCDs, each with a private L2, so XCD x keeps the heads
-    //      [x * per, (x + 1) * per) (all query heads of a KV head together).  Its items, ordered heaviest first
-    //      (later query tiles of a causal request see more keys), are dealt to its workgroups back and forth
-    //      (0 .. L-1, L-1 .. 0, ...): for the linear size profile of a causal sweep every workgroup gets the same
-    //      total.  Without the XCD split (head count not a multiple of 8) the same deal runs over all workgroups.
+    // ---- persistent workgroups, one per CU.  Consecutive workgroup ids land on consecutive XCDs, each with a
+    //      private L2, so XCD x keeps the heads [x * per, (x + 1) * per) (all query heads of a KV head together):
+    //      a queue of M items, heaviest first (later query tiles of a causal request see more keys).  All but the
+    //      last one or two rounds of a queue are dealt to the XCD's L workgroups back and forth (0 .. L-1,
+    //      L-1 .. 0, ...), which for the linear size profile of a causal sweep gives every workgroup the same
+    //      total.  XCDs do not run at quite the same speed, though, so the light items at the end of all queues
+    //      form one pool that every workgroup draws from, through a device-wide counter, as it becomes free:
+    //      a faster XCD takes more of them, and a workgroup whose dealt items were lighter a heavier one.  Pool
+    //      items mostly miss their XCD's L2, but they are few and small.  Without the XCD split (head count not
+    //      a multiple of 8) the same scheme runs with one queue over all workgroups.
     {
         const int P = gridDim.x, p = blockIdx.x;
         const bool split = a.heads_per_xcd > 0;
-        const int L = split ? P >> 3 : P, l = split ? p >> 3 : p;
-        const int width = split ? a.heads_per_xcd : a.Hq, h0 = split ? (p & 7) * a.heads_per_xcd : 0;
+        const int L = split ? P >> 3 : P, l = split ? p >> 3 : p, x = split ? p & 7 : 0;
+        const int width = split ? a.heads_per_xcd : a.Hq;
         const int M = a.q_tiles * width;
-        bool first = true;
-        for (int s = 0; s * L < M; ++s) {
-            const int m = s * L + ((s & 1) ? L - 1 - l : l);
-            if (m >= M) continue;
-            if (!first) wg_barrier();       // every wavefront is done with the LDS of the previous item
-            first = false;
-            process(m / width, h0 + m % width);
+        const int S = M > L ? max(1, (M - L) / L) : 1;            // rounds dealt statically; M <= L: one item each
+        const int pool_items = M > S * L ? (M - S * L) * (split ? 8 : 1) : 0;
+        int i_pool = 0;
+        bool drew = false;
+        for (int s = 0;; ++s) {
+            if (s > 0) wg_barrier();                                  // every wavefront is done with the LDS of the previous item
+            if (drew) i_pool = __builtin_amdgcn_readfirstlane(*lds_next);
+            int qu, m;
+            if (s < S) {
+                qu = x;
+                m = s * L + ((s & 1) ? L - 1 - l : l);
+            } else {
+                if (i_pool >= pool_items) break;
+                qu = split ? i_pool & 7 : 0;                          // the queues take turns: still heaviest first
+                m = S * L + (split ? i_pool >> 3 : i_pool);
+            }
+            if (m >= M) break;                                        // only when M <= L: fewer items than workgroups
+            int32_t* claim = (s >= S - 1 && pool_items > 0) ? a.queue : nullptr;
+            const bool ran = process(m / width, qu * width + m % width, claim);
+            drew = claim != nullptr;
+            if (drew && !ran) {                                       // no such query tile: it drew nothing
+                wg_barrier();                                         // everyone has read the previous answer
+                if (tid == 0) *lds_next = __hip_atomic_fetch_add(claim, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
     }
 }
+
+__global__ void prefill_reset_pool(int32_t* counter) { *counter = 0; }
 
 esp_status launch_prefill(const void* q, const void* k, const void* v, const int32_t* q_pos, const int32_t* kv_pos,
                           const int32_t* cu_q, const int32_t* cu_kv, int32_t batch, int32_t Tq, int32_t Tkv,
                           int32_t max_q, int32_t max_kv, int32_t Hq, int32_t Hkv, float softmax_scale,
                           int32_t causal, void* O, float* LSE, void* workspace, size_t workspace_bytes,
                           hipStream_t stream) {
-    (void)workspace; (void)workspace_bytes; (void)max_q; (void)max_kv;
+    (void)workspace_bytes; (void)max_q; (void)max_kv;
     PrefillArgs a;
     a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
     a.q_pos = q_pos; a.kv_pos = kv_pos; a.cu_q = cu_q; a.cu_kv = cu_kv;
@@ -727,6 +778,8 @@ esp_status launch_prefill(const void* q, const void* k, const void* v, const int
     // one workgroup per CU (a workgroup fills a CU's registers and LDS); fewer if there are fewer items
     a.heads_per_xcd = (Hkv % 8 == 0 && cus % 8 == 0 && items >= cus) ? Hq / 8 : 0;
     const unsigned grid = (unsigned)(items < cus ? items : cus);
+    a.queue = (int32_t*)workspace;
+    if (items > cus) hipLaunchKernelGGL(prefill_reset_pool, dim3(1), dim3(1), 0, stream, a.queue);
     hipLaunchKernelGGL(prefill_kernel, dim3(grid), dim3(kPfWaves * 64), 0, stream, a);
     return check_launch("prefill_kernel");
 }

@@ -43,10 +43,13 @@ def check_prefill_sampled(esp, pc, n_random_per_req, seed):
     parts, refs = [], []
     for si, s in enumerate(pc.shards):
         say(f"{pc.name} shard {si}: Tq={pc.Tq} Tkv={s.k.shape[0]} Hq={pc.Hq} Hkv={pc.Hkv} batch={pc.batch} samples={len(rows)}")
-        O, LSE = esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos,
-                                              None if single else pc.cu_q, None if single else s.cu_kv,
-                                              None if single else pc.max_q, None if single else s.max_kv,
-                                              softmax_scale=pc.scale, causal=pc.causal)
+        # outputs start as NaN, so that the no-NaN check below also proves every row was written by this launch
+        O = torch.full_like(pc.q, float("nan"))
+        LSE = torch.full((pc.Tq, pc.Hq), float("nan"), dtype=torch.float32, device=pc.q.device)
+        esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos,
+                                     None if single else pc.cu_q, None if single else s.cu_kv,
+                                     None if single else pc.max_q, None if single else s.max_kv,
+                                     softmax_scale=pc.scale, causal=pc.causal, O=O, LSE=LSE)
         torch.cuda.synchronize()
         cu_kv = wl.host_i32(s.cu_kv)
         Or, Lr = oracle.partial_attn(qb, wl.bits(s.k), wl.bits(s.v), qp, wl.host_i32(s.kv_pos), pc.scale, pc.causal,

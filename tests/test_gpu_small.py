@@ -36,10 +36,13 @@ def run_prefill_case(esp, pc, check_merged=True):
     parts, refs = [], []
     for si, s in enumerate(pc.shards):
         say(f"{pc.name} shard {si}: Tq={Tq} Tkv={s.k.shape[0]} Hq={Hq} Hkv={pc.Hkv} batch={pc.batch} causal={pc.causal}")
-        O, LSE = esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos,
-                                              None if single else pc.cu_q, None if single else s.cu_kv,
-                                              None if single else pc.max_q, None if single else s.max_kv,
-                                              softmax_scale=pc.scale, causal=pc.causal)
+        # outputs start as NaN: a row the launch never wrote cannot pass as a stale copy of an earlier result
+        O = torch.full_like(pc.q, float("nan"))
+        LSE = torch.full((Tq, Hq), float("nan"), dtype=torch.float32, device=pc.q.device)
+        esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos,
+                                     None if single else pc.cu_q, None if single else s.cu_kv,
+                                     None if single else pc.max_q, None if single else s.max_kv,
+                                     softmax_scale=pc.scale, causal=pc.causal, O=O, LSE=LSE)
         torch.cuda.synchronize()
         cu_kv = wl.host_i32(s.cu_kv)
         lo, hi = cu_kv[req_of_row[rows]], cu_kv[req_of_row[rows] + 1]
