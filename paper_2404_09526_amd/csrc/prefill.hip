@@ -111,7 +111,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     // each array's base folded into the per-lane register every operand read of the loop needs no address math.
     constexpr int kLdsV = 0, kLdsK = kLdsV + kStages * kTileBytes, kLdsPos = kLdsK + kStages * kKTileBytes,
                   kLdsQmm = kLdsPos + kStages * kBN * 4, kLdsSched = kLdsQmm + 2 * kPfWaves * 4,
-                  kLdsFlag = kLdsSched + kPfWaves * (1 + 2 * kPfWaves) * 4, kLdsTotal = kLdsFlag + 16;
+                  kLdsFlag = kLdsSched + kPfWaves * 64 * 8, kLdsTotal = kLdsFlag + 16;
     __shared__ __attribute__((aligned(1024))) unsigned char smem[kLdsTotal];
     unsigned char (*lds_k)[kKTileBytes] = (unsigned char (*)[kKTileBytes])(smem + kLdsK);
     unsigned char (*lds_v)[kTileBytes] = (unsigned char (*)[kTileBytes])(smem + kLdsV);
@@ -227,10 +227,17 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     // the first tiles are requested right away, so that their latency hides behind the Q load and the schedule
     // scan (tiles the scan later finds hidden are fetched for nothing, which is harmless: they exist)
     const int ragged_tile = tail_rows < kBN ? nkt - 1 : -8;          // index of the ragged last tile, if any
-    if (nkt > 0) { fetch_k(kreq, 0, 0 == ragged_tile); fetch_v(vreq, preq, 0, 0 == ragged_tile); }
-    if (nkt > 1) { fetch_k(kreq + tile_bytes, 1, 1 == ragged_tile); fetch_v(vreq + tile_bytes, preq + kBN, 1, 1 == ragged_tile); }
-    if (nkt > 2) fetch_k(kreq + 2 * tile_bytes, 2, 2 == ragged_tile);
-    if (nkt > 3) fetch_k(kreq + 3 * tile_bytes, 3, 3 == ragged_tile);
+    if (nkt > 4) {                                                   // the usual case, without a conditional in it
+        fetch_k(kreq, 0, false); fetch_v(vreq, preq, 0, false);
+        fetch_k(kreq + tile_bytes, 1, false); fetch_v(vreq + tile_bytes, preq + kBN, 1, false);
+        fetch_k(kreq + 2 * tile_bytes, 2, false);
+        fetch_k(kreq + 3 * tile_bytes, 3, false);
+    } else {
+        if (nkt > 0) { fetch_k(kreq, 0, 0 == ragged_tile); fetch_v(vreq, preq, 0, 0 == ragged_tile); }
+        if (nkt > 1) { fetch_k(kreq + tile_bytes, 1, 1 == ragged_tile); fetch_v(vreq + tile_bytes, preq + kBN, 1, 1 == ragged_tile); }
+        if (nkt > 2) fetch_k(kreq + 2 * tile_bytes, 2, 2 == ragged_tile);
+        if (nkt > 3) fetch_k(kreq + 3 * tile_bytes, 3, 3 == ragged_tile);
+    }
     // V stage 3 stands in for the tile before the first one (the loop multiplies the last chunk of tile j-1 at the
     // start of iteration j): zero it, since stale LDS contents could be NaN patterns; V(3) arrives there later
     {
@@ -288,56 +295,44 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     wave_qmin = __builtin_amdgcn_readfirstlane(wave_qmin);
     wave_qmax = __builtin_amdgcn_readfirstlane(wave_qmax);
     if (lane == 0) { lds_qmm[0][wave] = wave_qmin; lds_qmm[1][wave] = wave_qmax; }
-    wg_barrier();          // LDS only: the Q loads and tile transfers stay in flight
 
     // ---- tile schedule of this workgroup: n_vis = 1 + last tile some row can see (tiles before it that are
     //      hidden, possible only with unordered positions, are swept fully masked); first_mask = first tile
     //      this wavefront has to mask (every later tile is masked too, which is exact for ascending positions
     //      and merely redundant otherwise); n_need = 1 + last tile a row of this wavefront can see: beyond it
-    //      the wavefront only keeps up its share of the transfers and the barriers
+    //      the wavefront only keeps up its share of the transfers and the barriers.
+    //      The bounds of 512 tiles at a time (one per thread) go through LDS; every wavefront then reads them all,
+    //      64 per step, and wavefront-wide ballots turn its three tests into bit masks whose highest / lowest set
+    //      bit is the answer: no exchange of candidates, and one barrier for requests of up to 512 tiles.
     int n_vis = nkt, first_mask = nkt, n_need = nkt;
+    int2* lds_mm = (int2*)(smem + kLdsSched);
+    if (a.causal) lds_mm[tid] = mm_first;
+    wg_barrier();          // LDS only: the Q loads and tile transfers stay in flight
     if (a.causal) {
         int wg_qmax = lds_qmm[1][0];
 #pragma unroll
         for (int w = 1; w < kPfWaves; ++w) wg_qmax = max(wg_qmax, lds_qmm[1][w]);
-        int qmin_w[kPfWaves], qmax_w[kPfWaves];
-#pragma unroll
-        for (int w = 0; w < kPfWaves; ++w) { qmin_w[w] = lds_qmm[0][w]; qmax_w[w] = lds_qmm[1][w]; }
-        // every thread looks at tiles tid, tid + 512, ...; wavefront-wide ballots turn the per-tile tests into bit
-        // masks, whose highest / lowest set bit gives this wavefront's candidates (no atomics on shared words)
-        int last_vis = -1, fm[kPfWaves], lw[kPfWaves];
-#pragma unroll
-        for (int w = 0; w < kPfWaves; ++w) { fm[w] = nkt; lw[w] = -1; }
-        for (int t0 = wave * 64; t0 < nkt; t0 += kPfWaves * 64) {
-            const int2 mm = t0 == wave * 64 ? mm_first : tile_bounds(t0 + lane);
-            const uint64_t vis = __builtin_amdgcn_ballot_w64(mm.x <= wg_qmax);
-            if (vis) last_vis = t0 + 63 - __builtin_clzll(vis);
-#pragma unroll
-            for (int w = 0; w < kPfWaves; ++w) {
-                const uint64_t mk = __builtin_amdgcn_ballot_w64(mm.y > qmin_w[w]);
-                if (mk && fm[w] == nkt) fm[w] = t0 + __builtin_ctzll(mk);
-                const uint64_t vw = __builtin_amdgcn_ballot_w64(mm.x <= qmax_w[w]);
-                if (vw) lw[w] = t0 + 63 - __builtin_clzll(vw);
+        int last_vis = -1, fm = nkt, lw = -1;
+        for (int base = 0; base < nkt; base += kPfWaves * 64) {
+            if (base > 0) {
+                wg_barrier();                                       // everyone has read the previous 512
+                lds_mm[tid] = tile_bounds(base + tid);
+                wg_barrier();
+            }
+            const int cnt = min(kPfWaves * 64, nkt - base);
+            for (int t0 = 0; t0 < cnt; t0 += 64) {
+                const int2 mm = lds_mm[t0 + lane];                  // past the last tile: (INT_MAX, INT_MIN)
+                const uint64_t vis = __builtin_amdgcn_ballot_w64(mm.x <= wg_qmax);
+                if (vis) last_vis = base + t0 + 63 - __builtin_clzll(vis);
+                const uint64_t mk = __builtin_amdgcn_ballot_w64(mm.y > wave_qmin);
+                if (mk && fm == nkt) fm = base + t0 + __builtin_ctzll(mk);
+                const uint64_t vw = __builtin_amdgcn_ballot_w64(mm.x <= wave_qmax);
+                if (vw) lw = base + t0 + 63 - __builtin_clzll(vw);
             }
         }
-        // candidates of wavefront `wave` -> LDS (one row per scanning wavefront), then everyone combines the rows
-        int32_t (*cand)[1 + 2 * kPfWaves] = (int32_t (*)[1 + 2 * kPfWaves])(smem + kLdsSched);
-        if (lane == 0) {
-            cand[wave][0] = last_vis;
-#pragma unroll
-            for (int w = 0; w < kPfWaves; ++w) { cand[wave][1 + w] = fm[w]; cand[wave][1 + kPfWaves + w] = lw[w]; }
-        }
-        wg_barrier();
-        int lv = -1, fmk = nkt, lwk = -1;
-#pragma unroll
-        for (int sw = 0; sw < kPfWaves; ++sw) {
-            lv = max(lv, cand[sw][0]);
-            fmk = min(fmk, cand[sw][1 + wave]);
-            lwk = max(lwk, cand[sw][1 + kPfWaves + wave]);
-        }
-        n_vis = __builtin_amdgcn_readfirstlane(lv) + 1;
-        first_mask = __builtin_amdgcn_readfirstlane(fmk);
-        n_need = __builtin_amdgcn_readfirstlane(lwk) + 1;     // 1 + last tile a row of THIS wavefront can see
+        n_vis = last_vis + 1;
+        first_mask = fm;
+        n_need = lw + 1;
     }
 
     // ---- operand read offsets
