@@ -71,9 +71,8 @@ typedef int32_t esp_status;
  *     only to size the launch).
  *   O [Tq,Hq,D] bf16, LSE [Tq,Hq] float: written for every row.
  *   workspace: at least esp_prefill_workspace_bytes(...) bytes, 256-byte
- *     aligned; contents need not be preserved or initialised (the call
- *     clears what it uses on `stream` first).  Calls that may run at the
- *     same time need a workspace each.
+ *     aligned; contents need not be preserved or initialised.  Calls that
+ *     may run at the same time need a workspace each.
  * Positions may be in any order; ascending order inside a request lets whole
  * tiles be skipped or left unmasked.
  */

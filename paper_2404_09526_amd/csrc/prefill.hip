@@ -31,6 +31,10 @@
 //     the others apply the element-wise test kv_pos <= q_pos.
 #include <limits.h>
 
+#include <atomic>
+#include <chrono>
+#include <random>
+
 #include "esp_common.h"
 
 namespace esp {
@@ -47,7 +51,18 @@ typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4_t;
 
 static int32_t prefill_q_tiles_bound(int32_t Tq, int32_t batch) { return Tq / kBM + batch; }
 
-// Global scratch memory of the prefill path: one item counter (the first word of the block).
+// Global scratch memory of the prefill path: one 64-bit item counter (the first word of the block).  Every launch
+// gets a tag of its own, so that a counter left by an earlier launch, or never written, is told from the current
+// one without clearing it first (a clearing kernel ahead of each launch costs about 6 us).  Tags start at a random
+// 32-bit value per process: stale memory passes for the current launch's counter with probability 2^-32.
+static uint32_t next_launch_tag() {
+    static std::atomic<uint32_t> tag{[] {
+        uint32_t seed = (uint32_t)std::chrono::steady_clock::now().time_since_epoch().count();
+        try { seed ^= std::random_device{}(); } catch (...) {}
+        return seed;
+    }()};
+    return tag.fetch_add(1, std::memory_order_relaxed) + 1;
+}
 size_t prefill_workspace_bytes(int32_t Tq, int32_t Tkv, int32_t batch, int32_t Hq, int32_t Hkv) {
     (void)Tq; (void)Tkv; (void)batch; (void)Hq; (void)Hkv;
     return 256;
@@ -59,7 +74,8 @@ struct PrefillArgs {
     uint16_t* O; float* LSE;
     int32_t batch, Tq, Tkv, Hq, Hkv, causal;
     int32_t q_tiles, heads_per_xcd;   // upper bound of the number of query tiles; query heads per XCD (0: no split)
-    int32_t* queue;                   // counter of the item pool, zero at launch
+    unsigned long long* pool;         // counter of the item pool: launch tag (high word), draws so far (low word)
+    uint32_t tag;                     // this launch's tag
     float scale_log2;
 };
 
@@ -128,7 +144,22 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     //      counter (a device-wide atomic, issued when the sweep is done; its latency hides behind the epilogue) and
     //      leaves the counter's old value in LDS (lds_next), to be read after the next workgroup barrier.
     int32_t* lds_next = (int32_t*)(smem + kLdsFlag + 4);
-    auto process = [&](const int rank, const int h, int32_t* claim_from) {
+    // The pool counter needs no clearing between launches: its high word names the launch that counted in it.  A
+    // draw is one fetch-and-add; if the old value carries this launch's tag, its low word is the ticket.  If not
+    // (the first draws of a launch find the previous launch's count, or whatever a fresh workspace holds), the
+    // drawer starts this launch's count with a compare-and-swap, or draws again if another one has done so.
+    auto draw_finish = [&](unsigned long long* ctr, unsigned long long old) {
+        if ((uint32_t)(old >> 32) == a.tag) return (int)(uint32_t)old;
+        for (;;) {
+            unsigned long long cur = __hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((uint32_t)(cur >> 32) == a.tag)
+                return (int)(uint32_t)__hip_atomic_fetch_add(ctr, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (__hip_atomic_compare_exchange_strong(ctr, &cur, ((unsigned long long)a.tag << 32) | 1ULL, __ATOMIC_RELAXED,
+                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+                return 0;
+        }
+    };
+    auto process = [&](const int rank, const int h, unsigned long long* claim_from) {
     const int kvh = h / G;
     int q_lo, q_hi, kv_lo, kv_hi;   // rows of this query tile; rows of its request in the shard
     {
@@ -608,13 +639,13 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     wg_barrier();                                                   // everyone's flag write and last LDS reads are done
     // the draw of the next item: as late as possible, so that items go out in the order in which workgroups
     // really become free, and early enough for the answer to arrive while the results are written
-    int next_item = 0;
+    unsigned long long next_item = 0;
     if (claim_from && tid == 0) {
         // an index the compiler cannot see through: with a provably uniform address it rewrites the atomic into
         // its one-per-wavefront form, which needs the answer at once instead of after the epilogue
         int idx = 0;
         asm volatile("" : "+v"(idx));
-        next_item = __hip_atomic_fetch_add(claim_from + idx, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        next_item = __hip_atomic_fetch_add(claim_from + idx, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     if (__builtin_amdgcn_readfirstlane(*lds_unsafe) != 0) {
         float m_ref = -INFINITY;
@@ -703,7 +734,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     }
     if (row_ok && hi == 0)
         a.LSE[(int64_t)my_row * a.Hq + h] = ltot > 0.f ? (m_fin + __builtin_amdgcn_logf(ltot)) * kLn2 : -INFINITY;
-    if (claim_from && tid == 0) *lds_next = next_item;
+    if (claim_from && tid == 0) *lds_next = draw_finish(claim_from, next_item);
     return true;
     };
 
@@ -740,18 +771,17 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
                 m = S * L + (split ? i_pool >> 3 : i_pool);
             }
             if (m >= M) break;                                        // only when M <= L: fewer items than workgroups
-            int32_t* claim = (s >= S - 1 && pool_items > 0) ? a.queue : nullptr;
+            unsigned long long* claim = (s >= S - 1 && pool_items > 0) ? a.pool : nullptr;
             const bool ran = process(m / width, qu * width + m % width, claim);
             drew = claim != nullptr;
             if (drew && !ran) {                                       // no such query tile: it drew nothing
                 wg_barrier();                                         // everyone has read the previous answer
-                if (tid == 0) *lds_next = __hip_atomic_fetch_add(claim, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (tid == 0)
+                    *lds_next = draw_finish(claim, __hip_atomic_fetch_add(claim, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
             }
         }
     }
 }
-
-__global__ void prefill_reset_pool(int32_t* counter) { *counter = 0; }
 
 esp_status launch_prefill(const void* q, const void* k, const void* v, const int32_t* q_pos, const int32_t* kv_pos,
                           const int32_t* cu_q, const int32_t* cu_kv, int32_t batch, int32_t Tq, int32_t Tkv,
@@ -773,8 +803,8 @@ esp_status launch_prefill(const void* q, const void* k, const void* v, const int
     // one workgroup per CU (a workgroup fills a CU's registers and LDS); fewer if there are fewer items
     a.heads_per_xcd = (Hkv % 8 == 0 && cus % 8 == 0 && items >= cus) ? Hq / 8 : 0;
     const unsigned grid = (unsigned)(items < cus ? items : cus);
-    a.queue = (int32_t*)workspace;
-    if (items > cus) hipLaunchKernelGGL(prefill_reset_pool, dim3(1), dim3(1), 0, stream, a.queue);
+    a.pool = (unsigned long long*)workspace;
+    a.tag = next_launch_tag();
     hipLaunchKernelGGL(prefill_kernel, dim3(grid), dim3(kPfWaves * 64), 0, stream, a);
     return check_launch("prefill_kernel");
 }

@@ -24,7 +24,7 @@ def say(msg):
     print(f"[case] {msg}", flush=True)
 
 
-def run_prefill_case(esp, pc, check_merged=True):
+def run_prefill_case(esp, pc, check_merged=True, workspace=None):
     """Runs every shard through the HIP path, checks each partial and the merged result."""
     qb, qp = wl.bits(pc.q), wl.host_i32(pc.q_pos)
     cu_q = wl.host_i32(pc.cu_q)
@@ -42,7 +42,7 @@ def run_prefill_case(esp, pc, check_merged=True):
         esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos,
                                      None if single else pc.cu_q, None if single else s.cu_kv,
                                      None if single else pc.max_q, None if single else s.max_kv,
-                                     softmax_scale=pc.scale, causal=pc.causal, O=O, LSE=LSE)
+                                     softmax_scale=pc.scale, causal=pc.causal, O=O, LSE=LSE, workspace=workspace)
         torch.cuda.synchronize()
         cu_kv = wl.host_i32(s.cu_kv)
         lo, hi = cu_kv[req_of_row[rows]], cu_kv[req_of_row[rows] + 1]
@@ -320,6 +320,25 @@ def test_prefill_more_items_than_workgroups(esp, cuda, Hq, Hkv):
     pc = wl.contiguous_prefill(f"many-items-{Hq}/{Hkv}", Tq, 200, [(0, 330), (330, 700)], Hq, Hkv, 51, cuda)
     pc.q_pos[:] = torch.randint(0, 900, (Tq,), dtype=torch.int32, device=cuda)       # every tile sees a different part
     run_prefill_case(esp, pc)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("fill", ["zeros", "ones", "random"])
+def test_prefill_workspace_contents_do_not_matter(esp, cuda, fill):
+    """The workspace holds the counter of the item pool, which the call neither expects cleared nor clears: whatever
+    the block holds (nothing, all ones, noise, the count of the previous call: both shards reuse it), every item is
+    worked on exactly once.  More items than workgroups, so that the pool is in use; every query row is checked."""
+    Tq = 256 * 40 + 7
+    pc = wl.contiguous_prefill(f"workspace-{fill}", Tq, 150, [(0, 400), (400, 650)], 8, 8, 77, cuda)
+    pc.q_pos[:] = torch.randint(0, 800, (Tq,), dtype=torch.int32, device=cuda)
+    nbytes = esp.esp_prefill_workspace_bytes(Tq, 400, 1, 8, 8, 128)
+    if fill == "zeros":
+        ws = torch.zeros(nbytes, dtype=torch.uint8, device=cuda)
+    elif fill == "ones":
+        ws = torch.full((nbytes,), 255, dtype=torch.uint8, device=cuda)
+    else:
+        ws = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device=cuda, generator=torch.Generator(device=cuda).manual_seed(5))
+    run_prefill_case(esp, pc, workspace=ws)
 
 
 @pytest.mark.gpu
