@@ -120,7 +120,7 @@ def fit_model(esp, wl, torch, np, dev, batches=MODEL_FIT_BATCHES, Hq=32, Hkv=32,
     for bi, lens in enumerate(batches):
         pc = wl.striped_prefill("fit", lens, 1, 0, Hq, Hkv, 100 + bi, dev)
         sh = pc.shards[0]
-        ws = torch.empty(256, dtype=torch.uint8, device=dev)
+        ws = torch.empty(esp.esp_prefill_workspace_bytes(pc.Tq, sh.k.shape[0], pc.batch, pc.Hq, pc.Hkv, pc.D), dtype=torch.uint8, device=dev)
         O = torch.empty_like(pc.q); L = torch.empty((pc.Tq, pc.Hq), dtype=torch.float32, device=dev)
         single = pc.batch == 1
         run = lambda: esp.esp_partial_attn_prefill(pc.q, sh.k, sh.v, pc.q_pos, sh.kv_pos, None if single else pc.cu_q,

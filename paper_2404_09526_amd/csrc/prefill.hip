@@ -42,6 +42,7 @@ namespace esp {
 constexpr int kBM = 256;   // query rows per workgroup
 constexpr int kBN = 64;    // KV rows per tile
 constexpr int kPfWaves = 8;
+constexpr long long kSyncTicks = 15000;   // longest wait at a round start, in ticks of the 100 MHz wall clock (150 us)
 constexpr int kTileBytes = kBN * kHeadDim * 2;   // 16 KiB: a V tile in LDS, rows of 256 bytes
 constexpr int kKRow = 272;                       // LDS row pitch of a K tile: 256 bytes + 16 of padding
 constexpr int kKTileBytes = kBN * kKRow;         // 17 KiB = 17 transfers of 1 KiB
@@ -51,7 +52,8 @@ typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4_t;
 
 static int32_t prefill_q_tiles_bound(int32_t Tq, int32_t batch) { return Tq / kBM + batch; }
 
-// Global scratch memory of the prefill path: one 64-bit item counter (the first word of the block).  Every launch
+// Global scratch memory of the prefill path: one 64-bit item counter (the first word of the block), followed by the
+// arrival counts of the start-of-round waits (one per XCD and KV head; room for one per query head).  Every launch
 // gets a tag of its own, so that a counter left by an earlier launch, or never written, is told from the current
 // one without clearing it first (a clearing kernel ahead of each launch costs about 6 us).  Tags start at a random
 // 32-bit value per process: stale memory passes for the current launch's counter with probability 2^-32.
@@ -64,8 +66,8 @@ static uint32_t next_launch_tag() {
     return tag.fetch_add(1, std::memory_order_relaxed) + 1;
 }
 size_t prefill_workspace_bytes(int32_t Tq, int32_t Tkv, int32_t batch, int32_t Hq, int32_t Hkv) {
-    (void)Tq; (void)Tkv; (void)batch; (void)Hq; (void)Hkv;
-    return 256;
+    (void)Tq; (void)Tkv; (void)batch; (void)Hkv;
+    return ((size_t)8 * (1 + (size_t)(Hq > 0 ? Hq : 0)) + 255) / 256 * 256;   // pool counter + one count per query head
 }
 
 struct PrefillArgs {
@@ -76,6 +78,7 @@ struct PrefillArgs {
     int32_t q_tiles, heads_per_xcd;   // upper bound of the number of query tiles; query heads per XCD (0: no split)
     unsigned long long* pool;         // counter of the item pool: launch tag (high word), draws so far (low word)
     uint32_t tag;                     // this launch's tag
+    int32_t group_sync;               // workgroups sharing a KV head start their dealt rounds together
     float scale_log2;
 };
 
@@ -754,11 +757,34 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         const int L = split ? P >> 3 : P, l = split ? p >> 3 : p, x = split ? p & 7 : 0;
         const int width = split ? a.heads_per_xcd : a.Hq;
         const int M = a.q_tiles * width;
-        const int S = M > L ? max(1, (M - L) / L) : 1;            // rounds dealt statically; M <= L: one item each
+        // rounds dealt statically (M <= L: one item each).  With start-of-round waits everything is dealt: the items
+        // are long and alike, a pool could not even them out further, and its items would walk K/V alone
+        const int S = M <= L ? 1 : a.group_sync ? (M + L - 1) / L : max(1, (M - L) / L);
         const int pool_items = M > S * L ? (M - S * L) * (split ? 8 : 1) : 0;
         int i_pool = 0;
         bool drew = false;
         for (int s = 0;; ++s) {
+            // Long requests: the workgroups of an XCD that share a KV head (the same ones in every dealt round) walk
+            // K/V together, and the L2 serves all but the first of them, as long as they stay within the few dozen
+            // tiles it can hold per head.  Their items differ in length, so they would start the next round up to
+            // that far apart, and since all run at the same speed the gap never closes: K/V then comes from memory
+            // several times over.  So they wait for each other at the start of a dealt round: an arrival count per
+            // (XCD, KV head), tagged like the pool counter, and a wait that ends by itself after kSyncTicks.
+            if (a.group_sync && s >= 1 && (s + 1) * L <= M && tid == 0) {
+                const int m_next = s * L + ((s & 1) ? L - 1 - l : l);
+                unsigned long long* ctr = a.pool + 1 + x * width + (m_next % width) / G;
+                const uint32_t target = (uint32_t)(s * (L / width) * G);
+                const int before_me = draw_finish(ctr, __hip_atomic_fetch_add(ctr, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                if ((uint32_t)before_me + 1 < target) {
+                    const long long t0 = wall_clock64();
+                    for (;;) {
+                        const unsigned long long cur = __hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if ((uint32_t)(cur >> 32) == a.tag && (uint32_t)cur >= target) break;
+                        if (wall_clock64() - t0 > kSyncTicks) break;
+                        __builtin_amdgcn_s_sleep(16);
+                    }
+                }
+            }
             if (s > 0) wg_barrier();                                  // every wavefront is done with the LDS of the previous item
             if (drew) i_pool = __builtin_amdgcn_readfirstlane(*lds_next);
             int qu, m;
@@ -788,7 +814,7 @@ esp_status launch_prefill(const void* q, const void* k, const void* v, const int
                           int32_t max_q, int32_t max_kv, int32_t Hq, int32_t Hkv, float softmax_scale,
                           int32_t causal, void* O, float* LSE, void* workspace, size_t workspace_bytes,
                           hipStream_t stream) {
-    (void)workspace_bytes; (void)max_q; (void)max_kv;
+    (void)max_q; (void)max_kv;
     PrefillArgs a;
     a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
     a.q_pos = q_pos; a.kv_pos = kv_pos; a.cu_q = cu_q; a.cu_kv = cu_kv;
@@ -805,6 +831,10 @@ esp_status launch_prefill(const void* q, const void* k, const void* v, const int
     const unsigned grid = (unsigned)(items < cus ? items : cus);
     a.pool = (unsigned long long*)workspace;
     a.tag = next_launch_tag();
+    // start-of-round waits: one request with at least 512 KV tiles, XCD split, the same number of workgroups on
+    // every KV head of an XCD; the counters ((XCD, KV head), at most 8 x heads_per_xcd) follow the pool counter
+    a.group_sync = (a.heads_per_xcd > 0 && batch == 1 && Tkv >= 512 * kBN && (cus / 8) % a.heads_per_xcd == 0 &&
+                    8 * (1 + 8 * (size_t)a.heads_per_xcd) <= workspace_bytes) ? 1 : 0;
     hipLaunchKernelGGL(prefill_kernel, dim3(grid), dim3(kPfWaves * 64), 0, stream, a);
     return check_launch("prefill_kernel");
 }
