@@ -113,11 +113,11 @@ constexpr float kSumLimit = 1048576.f;  // 2^20: a tile's probability sum above 
 // waits are the explicit vmcnt waits in the kernel.
 __device__ __forceinline__ void load_to_lds_b128(uint32_t lds_addr, const void* gbase, uint32_t voff) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_addr), "v"(voff), "s"(gbase) : "memory");
+                 :: "s"(lds_addr), "v"(voff), "s"(gbase) : "memory", "m0");
 }
 __device__ __forceinline__ void load_to_lds_b32(uint32_t lds_addr, const void* gbase, uint32_t voff) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
-                 :: "s"(lds_addr), "v"(voff), "s"(gbase) : "memory");
+                 :: "s"(lds_addr), "v"(voff), "s"(gbase) : "memory", "m0");
 }
 template <int N>
 __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
