@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--retain", action="store_true",
                     help="proactive retention (scale-down during prefill): while each shard is attended, esp_kv_append keeps "
                          "ALL its rows in a token pool from a second stream; reports the overhead against prefill alone")
+    ap.add_argument("--from-pool", action="store_true",
+                    help="prefill over pool-resident shards: every shard's rows sit at random slots of a token pool and are "
+                         "attended through esp_partial_attn_prefill_pool; reports the overhead against the dense call")
     ap.add_argument("--fit-model", action="store_true",
                     help="also time whole-request causal prefill batches of several length mixes, fit the iteration-time model "
                          "(alpha + beta*sum(len) + gamma*sum(len^2)) with esp_fit_prefill_model and report its error")
@@ -314,6 +317,50 @@ def main():
         result["retain"] = {"ms_prefill_alone": t_plain, "ms_prefill_with_retention": t_ret,
                             "overhead_pct": 100.0 * (t_ret / t_plain - 1.0), "rows_retained": n_rows,
                             "bytes_moved": 2 * 2 * n_rows * pc.Hkv * pc.D * 2, "pool_matches": bool(ok)}
+    if args.from_pool:
+        # shards as a later chunk of a long prompt finds them: in the token pool, at scattered slots
+        n_rows = sum(s.k.shape[0] for s in pc.shards)
+        S = 1 << (n_rows - 1).bit_length()
+        kp = torch.zeros((S, pc.Hkv, pc.D), dtype=torch.bfloat16, device=dev)
+        vp = torch.zeros_like(kp)
+        perm = torch.from_numpy(np.random.default_rng(98).permutation(S)[:n_rows].astype(np.int32)).to(dev)
+        slots, o = [], 0
+        for s in pc.shards:
+            slots.append(perm[o:o + s.k.shape[0]].contiguous()); o += s.k.shape[0]
+            esp.esp_kv_append(s.k, s.v, slots[-1], kp, vp)
+        ws_pool = torch.empty(max(esp.esp_prefill_pool_workspace_bytes(pc.Tq, max(s.k.shape[0] for s in pc.shards), pc.batch, pc.Hq,
+                                                                       pc.Hkv, pc.D), 256), dtype=torch.uint8, device=dev)
+        pool_O = [torch.empty_like(x) for x in part_O]; pool_L = [torch.empty_like(x) for x in part_L]
+
+        def prefill_all(from_pool):
+            for i, s in enumerate(pc.shards):
+                if from_pool:
+                    esp.esp_partial_attn_prefill_pool(pc.q, kp, vp, slots[i], pc.q_pos, s.kv_pos,
+                                                      None if single else pc.cu_q, None if single else s.cu_kv,
+                                                      None if single else pc.max_q, None if single else s.max_kv,
+                                                      softmax_scale=pc.scale, causal=pc.causal, O=pool_O[i], LSE=pool_L[i],
+                                                      workspace=ws_pool)
+                else:
+                    esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos,
+                                                 None if single else pc.cu_q, None if single else s.cu_kv,
+                                                 None if single else pc.max_q, None if single else s.max_kv,
+                                                 softmax_scale=pc.scale, causal=pc.causal, O=part_O[i], LSE=part_L[i], workspace=ws_pf)
+
+        times = {}
+        for mode in (False, True, False, True):
+            prefill_all(mode); torch.cuda.synchronize()
+            e0, e1 = ev(), ev()
+            e0.record()
+            for _ in range(args.steps):
+                prefill_all(mode)
+            e1.record(); torch.cuda.synchronize()
+            times.setdefault(mode, []).append(e0.elapsed_time(e1) / args.steps)
+        t_dense, t_pool = min(times[False]), min(times[True])
+        same = all(torch.equal(a_, b_) for a_, b_ in zip(part_O, pool_O)) and all(torch.equal(a_, b_) for a_, b_ in zip(part_L, pool_L))
+        moved = 2 * 2 * n_rows * pc.Hkv * pc.D * 2                  # K and V, read from the pool and written to the staging rows
+        result["from_pool"] = {"ms_dense": t_dense, "ms_from_pool": t_pool, "overhead_pct": 100.0 * (t_pool / t_dense - 1.0),
+                               "rows": n_rows, "gather_bytes": moved, "gather_gbs": moved / ((t_pool - t_dense) * 1e-3) / 1e9,
+                               "same_bits_as_dense": bool(same)}
     if args.workload == "lwm7b" and os.path.exists(args.traffic_json):
         tr = json.load(open(args.traffic_json))
         result["roofline"]["traffic"] = tr.get("prefill_kernel")

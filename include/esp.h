@@ -145,6 +145,41 @@ esp_status esp_kv_append(
     void* stream);
 
 /*
+ * Dense view of pool-resident rows: the inverse of esp_kv_append.  The key-value
+ * rows a request keeps on this instance live in the token-granular pool at the
+ * slots the scheduler chose (Sec. 4.1, Fig. 7; Sec. 6 "unified distributed
+ * key-value cache pool"); a later prefill pass over them (the next chunk of a
+ * long prompt, a follow-up turn) needs them as one shard.
+ *   k[t] = k_pool[slot_idx[t]], v[t] = v_pool[slot_idx[t]]; a slot that is negative
+ *   or not below num_slots gives a row of zeros.  A pure copy of 16-bit patterns.
+ *
+ *   pools [num_slots,Hkv,D] bf16; slot_idx int32 [T]; k, v [T,Hkv,D] bf16 (written).
+ */
+esp_status esp_kv_gather(
+    const void* k_pool, const void* v_pool, const int32_t* slot_idx, int32_t T,
+    int64_t num_slots, int32_t Hkv, int32_t D, void* k, void* v, void* stream);
+
+/*
+ * esp_partial_attn_prefill over a shard that lives in the pool: row i of the
+ * shard is pool row slot_idx[i] (kv_pos[i] is its global position; cu_kv counts
+ * shard rows, i.e. entries of slot_idx).  Same results as esp_kv_gather followed
+ * by esp_partial_attn_prefill, which is how it is carried out: the gathered rows
+ * are staged in the workspace (2 * Tkv * Hkv * D * 2 bytes on top of the dense
+ * call's own block).  All other arguments as in esp_partial_attn_prefill.
+ */
+esp_status esp_partial_attn_prefill_pool(
+    const void* q, const void* k_pool, const void* v_pool, int64_t num_slots,
+    const int32_t* slot_idx, const int32_t* q_pos, const int32_t* kv_pos,
+    const int32_t* cu_q, const int32_t* cu_kv, int32_t batch,
+    int32_t Tq, int32_t Tkv, int32_t max_q, int32_t max_kv,
+    int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale, int32_t causal,
+    void* O, float* LSE,
+    void* workspace, size_t workspace_bytes, void* stream);
+
+size_t esp_prefill_pool_workspace_bytes(int32_t Tq, int32_t Tkv, int32_t batch,
+                                        int32_t Hq, int32_t Hkv, int32_t D);
+
+/*
  * Prefill batching plan (Sec. 5.4 "Batching", the dynamic program over sorted requests and sorted elastic
  * instances) -- host code, no GPU work; every pointer is HOST memory.
  *

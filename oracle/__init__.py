@@ -199,6 +199,24 @@ def kv_append(k, v, slot_idx, k_pool, v_pool):
         raise ValueError("oracle_kv_append: slot out of range")
 
 
+def kv_gather(k_pool, v_pool, slot_idx):
+    """Rows of the pool in the order of a slot list: the dense view of the key-value rows a request keeps in the
+    token-granular pool (Sec. 4.1 / Fig. 7; Sec. 6); the inverse of kv_append.  A slot that is negative or not below
+    the number of slots gives a row of zeros.  Returns (k, v) as uint16 [T, ...]."""
+    k_pool, v_pool = _bits(k_pool, "k_pool"), _bits(v_pool, "v_pool")
+    assert k_pool.shape == v_pool.shape
+    slot_idx = _i32(slot_idx)
+    assert slot_idx.ndim == 1
+    k = np.zeros((slot_idx.shape[0],) + k_pool.shape[1:], np.uint16)
+    v = np.zeros_like(k)
+    for t in range(slot_idx.shape[0]):
+        s = int(slot_idx[t])
+        if 0 <= s < k_pool.shape[0]:
+            k[t] = k_pool[s]
+            v[t] = v_pool[s]
+    return k, v
+
+
 def brute_force_attention(q, k, v, q_pos, kv_pos, scale, causal):
     """Dense-matrix softmax attention in numpy fp64, for pinning on tiny inputs only.
 

@@ -22,6 +22,7 @@ EXPORTS = (
     "esp_partial_attn_prefill", "esp_prefill_workspace_bytes", "esp_partial_attn_decode",
     "esp_decode_workspace_bytes", "esp_merge_partials", "esp_kv_append", "esp_last_error", "esp_version",
     "esp_plan_prefill_batches", "esp_fit_prefill_model",
+    "esp_kv_gather", "esp_partial_attn_prefill_pool", "esp_prefill_pool_workspace_bytes",
 )
 
 
@@ -50,6 +51,12 @@ def _load() -> ctypes.CDLL:
     L.esp_merge_partials.restype = i32
     L.esp_kv_append.argtypes = [vp, vp, vp, i32, vp, vp, i64, i32, i32, vp]
     L.esp_kv_append.restype = i32
+    L.esp_kv_gather.argtypes = [vp, vp, vp, i32, i64, i32, i32, vp, vp, vp]
+    L.esp_kv_gather.restype = i32
+    L.esp_partial_attn_prefill_pool.argtypes = [vp, vp, vp, i64] + [vp] * 5 + [i32] * 8 + [f32, i32, vp, vp, vp, sz, vp]
+    L.esp_partial_attn_prefill_pool.restype = i32
+    L.esp_prefill_pool_workspace_bytes.argtypes = [i32] * 6
+    L.esp_prefill_pool_workspace_bytes.restype = sz
     L.esp_plan_prefill_batches.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp]
     L.esp_plan_prefill_batches.restype = i32
     L.esp_fit_prefill_model.argtypes = [vp, vp, vp, vp, i32, vp]
@@ -206,6 +213,66 @@ def esp_kv_append(k, v, slot_idx, k_pool, v_pool) -> None:
         raise ValueError("append: shape mismatch")
     _check(lib.esp_kv_append(_ptr(k), _ptr(v), _ptr(slot_idx), T, _ptr(k_pool), _ptr(v_pool), k_pool.shape[0], Hkv, D,
                              _stream()))
+
+
+def esp_kv_gather(k_pool, v_pool, slot_idx, k=None, v=None):
+    """k[t] = k_pool[slot_idx[t]], v[t] = v_pool[slot_idx[t]]; a slot outside the pool gives a zero row.  Returns (k, v)."""
+    _dev(k_pool, torch.bfloat16, "k_pool"); _dev(v_pool, torch.bfloat16, "v_pool"); _dev(slot_idx, torch.int32, "slot_idx")
+    S, Hkv, D = k_pool.shape
+    T = slot_idx.numel()
+    if v_pool.shape != k_pool.shape or slot_idx.dim() != 1:
+        raise ValueError("gather: shape mismatch")
+    if k is None:
+        k = torch.empty((T, Hkv, D), dtype=torch.bfloat16, device=k_pool.device)
+    if v is None:
+        v = torch.empty((T, Hkv, D), dtype=torch.bfloat16, device=k_pool.device)
+    _dev(k, torch.bfloat16, "k"); _dev(v, torch.bfloat16, "v")
+    if k.shape != (T, Hkv, D) or v.shape != (T, Hkv, D):
+        raise ValueError("gather: output shape mismatch")
+    _check(lib.esp_kv_gather(_ptr(k_pool), _ptr(v_pool), _ptr(slot_idx), T, S, Hkv, D, _ptr(k), _ptr(v), _stream()))
+    return k, v
+
+
+def esp_prefill_pool_workspace_bytes(Tq, Tkv, batch, Hq, Hkv, D) -> int:
+    return int(lib.esp_prefill_pool_workspace_bytes(Tq, Tkv, batch, Hq, Hkv, D))
+
+
+def esp_partial_attn_prefill_pool(q, k_pool, v_pool, slot_idx, q_pos, kv_pos, cu_q=None, cu_kv=None, max_q=None, max_kv=None,
+                                  softmax_scale=None, causal=True, O=None, LSE=None, workspace=None):
+    """esp_partial_attn_prefill over the shard whose row i is pool row slot_idx[i].  Returns (O, LSE)."""
+    _dev(q, torch.bfloat16, "q"); _dev(k_pool, torch.bfloat16, "k_pool"); _dev(v_pool, torch.bfloat16, "v_pool")
+    _dev(slot_idx, torch.int32, "slot_idx"); _dev(q_pos, torch.int32, "q_pos"); _dev(kv_pos, torch.int32, "kv_pos")
+    Tq, Hq, D = q.shape
+    S, Hkv, Dk = k_pool.shape
+    Tkv = slot_idx.numel()
+    if Dk != D or v_pool.shape != k_pool.shape or q_pos.shape != (Tq,) or kv_pos.shape != (Tkv,) or slot_idx.dim() != 1:
+        raise ValueError("prefill (pool): shape mismatch")
+    batch = 1
+    if cu_q is not None:
+        _dev(cu_q, torch.int32, "cu_q"); _dev(cu_kv, torch.int32, "cu_kv")
+        batch = cu_q.numel() - 1
+        if cu_kv.numel() != batch + 1:
+            raise ValueError("prefill (pool): cu_q and cu_kv differ in length")
+        if max_q is None or max_kv is None:
+            raise ValueError("prefill (pool): max_q and max_kv are required with cu_q/cu_kv")
+    else:
+        max_q, max_kv = Tq, Tkv
+    if softmax_scale is None:
+        softmax_scale = D ** -0.5
+    if O is None:
+        O = torch.empty_like(q)
+    if LSE is None:
+        LSE = torch.empty((Tq, Hq), dtype=torch.float32, device=q.device)
+    _dev(O, torch.bfloat16, "O"); _dev(LSE, torch.float32, "LSE")
+    if O.shape != q.shape or LSE.shape != (Tq, Hq):
+        raise ValueError("prefill (pool): output shape mismatch")
+    if workspace is None:
+        workspace = _workspace(esp_prefill_pool_workspace_bytes(Tq, Tkv, batch, Hq, Hkv, D), q.device)
+    _check(lib.esp_partial_attn_prefill_pool(_ptr(q), _ptr(k_pool), _ptr(v_pool), S, _ptr(slot_idx), _ptr(q_pos), _ptr(kv_pos),
+                                             _ptr(cu_q), _ptr(cu_kv), batch, Tq, Tkv, int(max_q), int(max_kv), Hq, Hkv, D,
+                                             float(softmax_scale), 1 if causal else 0, _ptr(O), _ptr(LSE), _ptr(workspace),
+                                             workspace.numel(), _stream()))
+    return O, LSE
 
 
 def esp_plan_prefill_batches(req_len, free_slots, coefs, with_tables=False):

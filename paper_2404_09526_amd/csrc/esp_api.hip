@@ -72,6 +72,48 @@ esp_status esp_partial_attn_prefill(const void* q, const void* k, const void* v,
                           softmax_scale, causal, O, LSE, workspace, workspace_bytes, (hipStream_t)stream);
 }
 
+esp_status esp_kv_gather(const void* k_pool, const void* v_pool, const int32_t* slot_idx, int32_t T, int64_t num_slots,
+                         int32_t Hkv, int32_t D, void* k, void* v, void* stream) {
+    if (T < 0 || num_slots < 0 || Hkv <= 0) return fail(ESP_ERR_INVALID_ARG, "gather: negative size");
+    if (D != kHeadDim) return fail(ESP_ERR_UNSUPPORTED, "gather: head_dim %d unsupported (only 128)", D);
+    if (T == 0) return ESP_OK;
+    if (!k || !v || !slot_idx) return fail(ESP_ERR_INVALID_ARG, "gather: null pointer");
+    if (num_slots > 0 && (!k_pool || !v_pool)) return fail(ESP_ERR_INVALID_ARG, "gather: null pool");
+    return launch_kv_gather(k_pool, v_pool, slot_idx, T, num_slots, k, v, Hkv * D * 2, (hipStream_t)stream);
+}
+
+// the staging rows of the pool variant come first in its workspace, the dense call's own block after them
+static size_t pool_staging_bytes(int32_t Tkv, int32_t Hkv) {
+    size_t one = (size_t)(Tkv > 0 ? Tkv : 0) * (size_t)(Hkv > 0 ? Hkv : 0) * kHeadDim * 2;
+    return (one + 255) / 256 * 256;
+}
+
+size_t esp_prefill_pool_workspace_bytes(int32_t Tq, int32_t Tkv, int32_t batch, int32_t Hq, int32_t Hkv, int32_t D) {
+    (void)D;
+    return 2 * pool_staging_bytes(Tkv, Hkv) + prefill_workspace_bytes(Tq, Tkv, batch, Hq, Hkv);
+}
+
+esp_status esp_partial_attn_prefill_pool(const void* q, const void* k_pool, const void* v_pool, int64_t num_slots,
+                                         const int32_t* slot_idx, const int32_t* q_pos, const int32_t* kv_pos,
+                                         const int32_t* cu_q, const int32_t* cu_kv, int32_t batch, int32_t Tq,
+                                         int32_t Tkv, int32_t max_q, int32_t max_kv, int32_t Hq, int32_t Hkv, int32_t D,
+                                         float softmax_scale, int32_t causal, void* O, float* LSE, void* workspace,
+                                         size_t workspace_bytes, void* stream) {
+    if (Tkv < 0 || num_slots < 0 || Hkv <= 0) return fail(ESP_ERR_INVALID_ARG, "prefill (pool): negative size");
+    if (D != kHeadDim) return fail(ESP_ERR_UNSUPPORTED, "prefill (pool): head_dim %d unsupported (only 128)", D);
+    if (Tkv > 0 && !slot_idx) return fail(ESP_ERR_INVALID_ARG, "prefill (pool): null slot_idx");
+    const size_t stage = pool_staging_bytes(Tkv, Hkv);
+    const size_t need = esp_prefill_pool_workspace_bytes(Tq, Tkv, batch, Hq, Hkv, D);
+    if (!workspace || workspace_bytes < need)
+        return fail(ESP_ERR_WORKSPACE, "prefill (pool): workspace needs %zu bytes, got %zu", need, workspace ? workspace_bytes : (size_t)0);
+    if ((uintptr_t)workspace & 255) return fail(ESP_ERR_WORKSPACE, "prefill (pool): workspace not 256-byte aligned");
+    char* ws = (char*)workspace;
+    esp_status st = esp_kv_gather(k_pool, v_pool, slot_idx, Tkv, num_slots, Hkv, D, ws, ws + stage, stream);
+    if (st != ESP_OK) return st;
+    return esp_partial_attn_prefill(q, ws, ws + stage, q_pos, kv_pos, cu_q, cu_kv, batch, Tq, Tkv, max_q, max_kv, Hq, Hkv, D,
+                                    softmax_scale, causal, O, LSE, ws + 2 * stage, workspace_bytes - 2 * stage, stream);
+}
+
 esp_status esp_partial_attn_decode(const void* q, const void* k_pool, const void* v_pool, int64_t num_slots,
                                    const int32_t* slot_idx, const int32_t* seq_offsets, int32_t B,
                                    int32_t total_tokens, int32_t max_len, int32_t Hq, int32_t Hkv, int32_t D,

@@ -42,6 +42,8 @@ struct MergeArgs {
 };
 esp_status launch_kv_append(const void* k, const void* v, const int32_t* slot_idx, int32_t T, void* k_pool,
                             void* v_pool, int32_t row_bytes, hipStream_t stream);
+esp_status launch_kv_gather(const void* k_pool, const void* v_pool, const int32_t* slot_idx, int32_t T, int64_t num_slots,
+                            void* k, void* v, int32_t row_bytes, hipStream_t stream);
 esp_status launch_merge(const MergeArgs& parts, int32_t P, int64_t pairs, void* O, float* LSE_out,
                         hipStream_t stream);
 

@@ -322,6 +322,67 @@ def test_prefill_more_items_than_workgroups(esp, cuda, Hq, Hkv):
     run_prefill_case(esp, pc)
 
 
+def pool_image(rng, shard, num_slots):
+    """Host pool arrays holding the shard's rows at random distinct slots (built by the oracle's own scatter), plus noise
+    in every other slot; returns (k_pool, v_pool, slots) as numpy arrays."""
+    kb, vb = wl.bits(shard.k), wl.bits(shard.v)
+    kp = rng.integers(0, 65536, (num_slots,) + kb.shape[1:]).astype(np.uint16); vp = rng.integers(0, 65536, kp.shape).astype(np.uint16)
+    kp &= 0x3FFF; vp &= 0x3FFF                                   # noise, but finite bf16 values
+    slots = rng.permutation(num_slots)[: kb.shape[0]].astype(np.int32)
+    oracle.kv_append(kb, vb, slots, kp, vp)
+    return kp, vp, slots
+
+
+def test_kv_gather_bit_exact(esp, cuda):
+    """Every gathered row against the oracle, bit for bit; slots outside the pool (negative, too large) give zero rows."""
+    rng = np.random.default_rng(31)
+    S, T, Hkv = 5000, 3001, 4
+    kp = rng.integers(0, 65536, (S, Hkv, 128)).astype(np.uint16); vp = rng.integers(0, 65536, (S, Hkv, 128)).astype(np.uint16)
+    slots = rng.integers(0, S, T).astype(np.int32)                # repeats allowed
+    slots[::11] = -1; slots[5::97] = S; slots[7::101] = S + 12345
+    say(f"gather: S={S} T={T} Hkv={Hkv}")
+    to = lambda a: torch.from_numpy(a.view(np.int16)).to(cuda).view(torch.bfloat16)
+    k, v = esp.esp_kv_gather(to(kp), to(vp), torch.from_numpy(slots).to(cuda))
+    torch.cuda.synchronize()
+    kr, vr = oracle.kv_gather(kp, vp, slots)
+    assert np.array_equal(wl.bits(k), kr) and np.array_equal(wl.bits(v), vr)
+    k0, v0 = esp.esp_kv_gather(to(kp), to(vp), torch.zeros(0, dtype=torch.int32, device=cuda))
+    assert k0.shape == (0, Hkv, 128) and v0.shape == (0, Hkv, 128)
+
+
+@pytest.mark.parametrize("layout", ["one-request", "var-len-gqa"])
+def test_prefill_over_pool_resident_rows(esp, cuda, layout):
+    """The shard's rows live in a token pool at random slots; the call over (pool, slot list) must give what the
+    oracle gives on its own gathered rows.  Every query row is checked."""
+    rng = np.random.default_rng(41)
+    if layout == "one-request":
+        pc = wl.contiguous_prefill("pool-1req", 300, 400, [(0, 700)], 4, 4, 61, cuda)
+    else:
+        pc = wl.striped_prefill("pool-varlen", [70, 257, 130], 2, 1, 8, 2, 62, cuda)
+    qb, qp = wl.bits(pc.q), wl.host_i32(pc.q_pos)
+    cu_q = wl.host_i32(pc.cu_q)
+    Tq, Hq, D = pc.q.shape
+    rows = np.repeat(np.arange(Tq, dtype=np.int64), Hq); heads = np.tile(np.arange(Hq, dtype=np.int64), Tq)
+    req_of_row = np.searchsorted(cu_q, np.arange(Tq), side="right") - 1
+    single = pc.batch == 1
+    to = lambda a: torch.from_numpy(a.view(np.int16)).to(cuda).view(torch.bfloat16)
+    for si, s in enumerate(pc.shards):
+        S = 2048
+        kp, vp, slots = pool_image(rng, s, S)
+        say(f"{pc.name} shard {si}: Tq={Tq} Tkv={len(slots)} pool={S} Hq={Hq} Hkv={pc.Hkv} batch={pc.batch}")
+        O = torch.full_like(pc.q, float("nan")); LSE = torch.full((Tq, Hq), float("nan"), dtype=torch.float32, device=cuda)
+        esp.esp_partial_attn_prefill_pool(pc.q, to(kp), to(vp), torch.from_numpy(slots).to(cuda), pc.q_pos, s.kv_pos,
+                                          None if single else pc.cu_q, None if single else s.cu_kv,
+                                          None if single else pc.max_q, None if single else s.max_kv,
+                                          softmax_scale=pc.scale, causal=pc.causal, O=O, LSE=LSE)
+        torch.cuda.synchronize()
+        kg, vg = oracle.kv_gather(kp, vp, slots)
+        cu_kv = wl.host_i32(s.cu_kv)
+        lo, hi = cu_kv[req_of_row[rows]], cu_kv[req_of_row[rows] + 1]
+        Or, Lr = oracle.partial_attn(qb, kg, vg, qp, wl.host_i32(s.kv_pos), pc.scale, pc.causal, rows, heads, lo, hi)
+        check_o_lse(O.float().cpu().numpy().reshape(-1, D), LSE.cpu().numpy().reshape(-1), Or, Lr, f"{pc.name} shard {si}")
+
+
 @pytest.mark.gpu
 @pytest.mark.parametrize("fill", ["zeros", "ones", "random"])
 def test_prefill_workspace_contents_do_not_matter(esp, cuda, fill):

@@ -248,6 +248,36 @@ def test_append_is_an_exact_scatter():
         oracle.kv_append(k[:1], v[:1], np.array([S], np.int32), kp, vp)
 
 
+def test_gather_is_the_inverse_view_of_append():
+    """kv_gather against what fixes it: a hand-written case, the round trip through the C scatter, zero rows for
+    slots outside the pool, and the decode routine (which reads the pool through the same slot list by itself)."""
+    # by hand: pool rows 0..3 hold 10, 11, 12, 13 (K) and 20, 21, 22, 23 (V)
+    kp = np.array([[10], [11], [12], [13]], np.uint16); vp = kp + 10
+    k, v = oracle.kv_gather(kp, vp, np.array([2, 0, -1, 3, 4, 2], np.int32))
+    assert k[:, 0].tolist() == [12, 10, 0, 13, 0, 12] and v[:, 0].tolist() == [22, 20, 0, 23, 0, 22]
+    # round trip: rows scattered by kv_append (the C routine) come back in their own order
+    rng = np.random.default_rng(14)
+    S, T, row = 200, 60, (2, 16)
+    kpool = np.zeros((S,) + row, np.uint16); vpool = np.zeros_like(kpool)
+    kr = rng.integers(1, 65536, (T,) + row).astype(np.uint16); vr = rng.integers(1, 65536, (T,) + row).astype(np.uint16)
+    slots = rng.permutation(S)[:T].astype(np.int32)
+    oracle.kv_append(kr, vr, slots, kpool, vpool)
+    kg, vg = oracle.kv_gather(kpool, vpool, slots)
+    np.testing.assert_array_equal(kg, kr); np.testing.assert_array_equal(vg, vr)
+    dropped = slots.copy(); dropped[::5] = -3
+    kg, vg = oracle.kv_gather(kpool, vpool, dropped)
+    assert (kg[::5] == 0).all() and (vg[::5] == 0).all()
+    np.testing.assert_array_equal(np.delete(kg, np.s_[::5], 0), np.delete(kr, np.s_[::5], 0))
+    # attention over the gathered rows = the decode routine over the slot list
+    Hq, Hkv = 4, 2
+    kpool = rand_bits(rng, (S, Hkv, D)); vpool = rand_bits(rng, (S, Hkv, D)); q = rand_bits(rng, (1, Hq, D))
+    sl = rng.permutation(S)[:37].astype(np.int32)
+    Od, Ld = oracle.partial_attn_decode_all(q, kpool, vpool, sl, np.array([0, 37], np.int32), 0.3)
+    kg, vg = oracle.kv_gather(kpool, vpool, sl)
+    Og, Lg = oracle.partial_attn_all(q, kg, vg, np.zeros(1, np.int32), np.zeros(37, np.int32), 0.3, False)
+    np.testing.assert_allclose(Od[0], Og[0], atol=1e-13); np.testing.assert_allclose(Ld[0], Lg[0], atol=1e-13)
+
+
 # ------------------------------------------------------------------ P11: bytes per token (Sec. 1, Sec. 4.1)
 def test_kv_bytes_per_token_matches_the_papers_488GB():
     layers, Hkv, d = 32, 32, 128          # LWM-1M-Text = Llama-2-7B shape (Sec. 7.1)
