@@ -4,10 +4,11 @@
 // in Sec. 6).  Emits the un-merged output, normalised within the shard, and its log-sum-exp.
 //
 // Mapping to gfx950 (64-wide wavefronts, MFMA 32x32x16 bf16, 160 KiB LDS):
-//   * one persistent workgroup of 8 wavefronts per CU works through a fixed list of items; an
-//     item is 256 query rows of one head: each wavefront owns 32 rows and keeps their Q fragment
-//     (B operand), the softmax state and the fp32 output accumulator in registers for the whole
-//     KV sweep;
+//   * one persistent workgroup of 8 wavefronts per CU works through items; an item is 256 query
+//     rows of one head: each wavefront owns 32 rows and keeps their Q fragment (B operand), the
+//     softmax state and the fp32 output accumulator in registers for the whole KV sweep.  Most
+//     items are dealt to the workgroups beforehand, the light ones at the end are drawn from a
+//     device-wide counter as workgroups become free (see the item loop at the end of the kernel);
 //   * K/V tiles of 64 rows are fetched straight from global memory into a 4-stage LDS ring
 //     (global_load ... lds, no register staging), K four tiles and V two tiles ahead of their use;
 //   * the K tile is the A operand of S^T = K Q^T, so a lane ends up with scores of ONE query
@@ -28,7 +29,8 @@
 //   * the minimum / maximum position of every KV tile (found by the workgroup itself while its
 //     first tiles are in flight) decide: tiles past the last one any row can see are never
 //     processed; tiles below every row of a wavefront run the branch-free "plain" iteration;
-//     the others apply the element-wise test kv_pos <= q_pos.
+//     the others apply the element-wise test kv_pos <= q_pos; past the last tile any of its own
+//     rows can see a wavefront stops its arithmetic and only keeps up transfers and barriers.
 #include <limits.h>
 
 #include <atomic>
