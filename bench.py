@@ -36,6 +36,10 @@ def parse():
     ap.add_argument("--retain", action="store_true",
                     help="proactive retention (scale-down during prefill): while each shard is attended, esp_kv_append keeps "
                          "ALL its rows in a token pool from a second stream; reports the overhead against prefill alone")
+    ap.add_argument("--multi-master", action="store_true",
+                    help="distributed decoding with several masters on one GPU: this instance decodes the requests it is master "
+                         "of while the queries of the other masters' requests arrive (host-to-device copies on a second stream), "
+                         "then decodes those and sends their results back; reports the time against one decode call over all")
     ap.add_argument("--from-pool", action="store_true",
                     help="prefill over pool-resident shards: every shard's rows sit at random slots of a token pool and are "
                          "attended through esp_partial_attn_prefill_pool; reports the overhead against the dense call")
@@ -317,6 +321,63 @@ def main():
         result["retain"] = {"ms_prefill_alone": t_plain, "ms_prefill_with_retention": t_ret,
                             "overhead_pct": 100.0 * (t_ret / t_plain - 1.0), "rows_retained": n_rows,
                             "bytes_moved": 2 * 2 * n_rows * pc.Hkv * pc.D * 2, "pool_matches": bool(ok)}
+    if args.multi_master and dc is not None and dc.B >= 2:
+        # Sec. 4.2 / Fig. 8: every instance is master of some requests (it has their queries) and a helper for the
+        # rest, whose queries come from their masters and whose partial results go back to them
+        h = dc.B // 2
+        off_h = int(dc.seq_offsets[h].item())
+        own_off = dc.seq_offsets[:h + 1].contiguous()
+        peer_off = (dc.seq_offsets[h:] - off_h).contiguous()
+        own_slots, peer_slots = dc.slot_idx[:off_h].contiguous(), dc.slot_idx[off_h:].contiguous()
+        lens = dc.lens
+        ml_own, ml_peer = int(lens[:h].max()), int(lens[h:].max())
+        q_host = dc.q[h:].cpu().pin_memory()                       # the other masters' queries, as they come off the wire
+        q_peer = torch.empty_like(dc.q[h:])
+        O_own, L_own = torch.empty_like(dc.q[:h]), torch.empty((h, dc.Hq), dtype=torch.float32, device=dev)
+        O_peer, L_peer = torch.empty_like(dc.q[h:]), torch.empty((dc.B - h, dc.Hq), dtype=torch.float32, device=dev)
+        O_back = torch.empty(O_peer.shape, dtype=O_peer.dtype).pin_memory(); L_back = torch.empty(L_peer.shape, dtype=L_peer.dtype).pin_memory()
+        ws_own = torch.empty(esp.esp_decode_workspace_bytes(h, off_h, ml_own, dc.Hq, dc.Hkv, dc.D), dtype=torch.uint8, device=dev)
+        ws_peer = torch.empty(esp.esp_decode_workspace_bytes(dc.B - h, dc.total_tokens - off_h, ml_peer, dc.Hq, dc.Hkv, dc.D),
+                              dtype=torch.uint8, device=dev)
+        mO_own, mL_own = torch.empty_like(O_own), torch.empty_like(L_own)
+        wire = torch.cuda.Stream()
+
+        def masters():
+            main = torch.cuda.current_stream()
+            wire.wait_stream(main)
+            with torch.cuda.stream(wire):
+                q_peer.copy_(q_host, non_blocking=True)           # peers' queries arrive while the own requests are decoded
+            esp.esp_partial_attn_decode(dc.q[:h], dc.k_pool, dc.v_pool, own_slots, own_off, ml_own, softmax_scale=dc.scale,
+                                        O=O_own, LSE=L_own, workspace=ws_own)
+            main.wait_stream(wire)
+            esp.esp_partial_attn_decode(q_peer, dc.k_pool, dc.v_pool, peer_slots, peer_off, ml_peer, softmax_scale=dc.scale,
+                                        O=O_peer, LSE=L_peer, workspace=ws_peer)
+            wire.wait_stream(main)
+            with torch.cuda.stream(wire):
+                O_back.copy_(O_peer, non_blocking=True); L_back.copy_(L_peer, non_blocking=True)   # results go back to their masters
+            esp.esp_merge_partials([O_own] + [p[:h] for p in dc.peer_O], [L_own] + [p[:h] for p in dc.peer_LSE], O=mO_own, LSE=mL_own)
+            main.wait_stream(wire)
+
+        def one_call():
+            esp.esp_partial_attn_decode(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, max_len,
+                                        softmax_scale=dc.scale, O=dO, LSE=dL, workspace=ws_dc)
+            esp.esp_merge_partials([dO] + list(dc.peer_O), [dL] + list(dc.peer_LSE), O=mO, LSE=mL)
+
+        times = {}
+        for fn in (one_call, masters, one_call, masters):
+            fn(); torch.cuda.synchronize()
+            e0, e1 = ev(), ev()
+            e0.record()
+            for _ in range(args.steps):
+                fn()
+            e1.record(); torch.cuda.synchronize()
+            times.setdefault(fn.__name__, []).append(e0.elapsed_time(e1) / args.steps)
+        t_one, t_mm = min(times["one_call"]), min(times["masters"])
+        diff = max(float((O_own.float() - dO[:h].float()).abs().max()), float((O_peer.float() - dO[h:].float()).abs().max()),
+                   float((O_back.float() - dO[h:].float().cpu()).abs().max()))
+        result["multi_master"] = {"ms_one_decode_call": t_one, "ms_two_masters": t_mm, "overhead_pct": 100.0 * (t_mm / t_one - 1.0),
+                                  "own_requests": h, "peer_requests": dc.B - h, "query_bytes_in": q_host.numel() * 2,
+                                  "result_bytes_out": O_back.numel() * 2 + L_back.numel() * 4, "max_abs_diff_vs_one_call": diff}
     if args.from_pool:
         # shards as a later chunk of a long prompt finds them: in the token pool, at scattered slots
         n_rows = sum(s.k.shape[0] for s in pc.shards)

@@ -119,6 +119,22 @@ def test_config1_decode_append_merge(esp, cuda):
                 Lref.reshape(-1), "C1 merge")
 
 
+def test_decode_in_two_master_groups(esp, cuda):
+    """Distributed decoding with several masters (Sec. 4.2): the requests this instance is master of and the ones it
+    helps with are decoded by separate calls, each over its own part of the slot list; both against the oracle."""
+    import dataclasses
+    dc = wl.config1_decode(cuda)
+    h = dc.B // 2
+    off = wl.host_i32(dc.seq_offsets)
+    for name, lo, hi in (("own", 0, h), ("helped", h, dc.B)):
+        sub = dataclasses.replace(
+            dc, name=f"{dc.name}-{name}", lens=dc.lens[lo:hi], q=dc.q[lo:hi].contiguous(),
+            slot_idx=dc.slot_idx[int(off[lo]):int(off[hi])].contiguous(),
+            seq_offsets=(dc.seq_offsets[lo:hi + 1] - int(off[lo])).contiguous(),
+            host_rows={b - lo: r for b, r in dc.host_rows.items() if lo <= b < hi})
+        run_decode_case(esp, sub)
+
+
 # ------------------------------------------------------------------ prefill: layouts and edge cases
 @pytest.mark.parametrize("r_q", [0, 1, 2, 3])
 def test_striped_all_offsets(esp, cuda, r_q):
