@@ -54,8 +54,9 @@ typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4_t;
 
 static int32_t prefill_q_tiles_bound(int32_t Tq, int32_t batch) { return Tq / kBM + batch; }
 
-// Global scratch memory of the prefill path: one 64-bit item counter (the first word of the block), followed by the
-// arrival counts of the start-of-round waits (one per XCD and KV head; room for one per query head).  Every launch
+// Global scratch memory of the prefill path: one 64-bit item counter (the first word of the block, the second is
+// spare) and the arrival counts of the start-of-round waits (one per XCD and KV head; room for one per query head).
+// Every launch
 // gets a tag of its own, so that a counter left by an earlier launch, or never written, is told from the current
 // one without clearing it first (a clearing kernel ahead of each launch costs about 6 us).  Tags start at a random
 // 32-bit value per process: stale memory passes for the current launch's counter with probability 2^-32.
@@ -65,11 +66,12 @@ static uint32_t next_launch_tag() {
         try { seed ^= std::random_device{}(); } catch (...) {}
         return seed;
     }()};
-    return tag.fetch_add(1, std::memory_order_relaxed) + 1;
+    const uint32_t t = tag.fetch_add(1, std::memory_order_relaxed) + 1;
+    return t ? t : tag.fetch_add(1, std::memory_order_relaxed) + 1;   // never 0: cleared counters carry tag 0
 }
 size_t prefill_workspace_bytes(int32_t Tq, int32_t Tkv, int32_t batch, int32_t Hq, int32_t Hkv) {
     (void)Tq; (void)Tkv; (void)batch; (void)Hkv;
-    return ((size_t)8 * (1 + (size_t)(Hq > 0 ? Hq : 0)) + 255) / 256 * 256;   // pool counter + one count per query head
+    return ((size_t)8 * (2 + (size_t)(Hq > 0 ? Hq : 0)) + 255) / 256 * 256;   // pool and exit counters + one count per query head
 }
 
 struct PrefillArgs {
@@ -774,21 +776,30 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
             // (XCD, KV head), tagged like the pool counter, and a wait that ends by itself after kSyncTicks.
             if (a.group_sync && s >= 1 && (s + 1) * L <= M && tid == 0) {
                 const int m_next = s * L + ((s & 1) ? L - 1 - l : l);
-                unsigned long long* ctr = a.pool + 1 + x * width + (m_next % width) / G;
+                unsigned long long* ctr = a.pool + 2 + x * width + (m_next % width) / G;
                 const uint32_t target = (uint32_t)(s * (L / width) * G);
                 const int before_me = draw_finish(ctr, __hip_atomic_fetch_add(ctr, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
                 if ((uint32_t)before_me + 1 < target) {
                     const long long t0 = wall_clock64();
                     for (;;) {
                         const unsigned long long cur = __hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        if ((uint32_t)(cur >> 32) == a.tag && (uint32_t)cur >= target) break;
+                        // a count that is no longer this launch's was cleared by the last arrival (see below)
+                        if ((uint32_t)(cur >> 32) != a.tag || (uint32_t)cur >= target) break;
                         if (wall_clock64() - t0 > kSyncTicks) break;
                         __builtin_amdgcn_s_sleep(16);
                     }
+                } else if ((s + 2) * L > M) {
+                    // the last arrival of the last round that waits clears the count: a launch replayed from a
+                    // captured graph carries the tag it was recorded with and must not find its own earlier counts
+                    __hip_atomic_store(ctr, 0ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
             if (s > 0) wg_barrier();                                  // every wavefront is done with the LDS of the previous item
             if (drew) i_pool = __builtin_amdgcn_readfirstlane(*lds_next);
+            // every workgroup draws once per item from its last dealt one on, until a draw comes back empty: P draws
+            // plus one per pool item.  The very last one clears the counter (replayed launches, see above).
+            if (drew && i_pool == pool_items + P - 1 && tid == 0)
+                __hip_atomic_store(a.pool, 0ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             int qu, m;
             if (s < S) {
                 qu = x;
@@ -836,7 +847,7 @@ esp_status launch_prefill(const void* q, const void* k, const void* v, const int
     // start-of-round waits: one request with at least 512 KV tiles, XCD split, the same number of workgroups on
     // every KV head of an XCD; the counters ((XCD, KV head), at most 8 x heads_per_xcd) follow the pool counter
     a.group_sync = (a.heads_per_xcd > 0 && batch == 1 && Tkv >= 512 * kBN && (cus / 8) % a.heads_per_xcd == 0 &&
-                    8 * (1 + 8 * (size_t)a.heads_per_xcd) <= workspace_bytes) ? 1 : 0;
+                    8 * (2 + 8 * (size_t)a.heads_per_xcd) <= workspace_bytes) ? 1 : 0;
     hipLaunchKernelGGL(prefill_kernel, dim3(grid), dim3(kPfWaves * 64), 0, stream, a);
     return check_launch("prefill_kernel");
 }

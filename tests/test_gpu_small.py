@@ -419,6 +419,43 @@ def test_prefill_workspace_contents_do_not_matter(esp, cuda, fill):
 
 
 @pytest.mark.gpu
+def test_prefill_replayed_from_a_captured_graph(esp, cuda):
+    """A prefill call recorded into a graph and replayed: the replays carry the recorded launch's arguments, counters'
+    tag included, and must still work every item exactly once.  Replays alternate with eager calls on the same
+    workspace and with host synchronisation; every replay is compared bit for bit with the eager result (which the
+    other tests check against the oracle).  More items than workgroups, so that the item pool is in use."""
+    Tq = 256 * 40 + 7
+    pc = wl.contiguous_prefill("graph-replay", Tq, 150, [(0, 400)], 8, 8, 78, cuda)
+    pc.q_pos[:] = torch.randint(0, 800, (Tq,), dtype=torch.int32, device=cuda)
+    s = pc.shards[0]
+    ws = torch.empty(esp.esp_prefill_workspace_bytes(Tq, 400, 1, 8, 8, 128), dtype=torch.uint8, device=cuda)
+    nan_like = lambda t: torch.full_like(t, float("nan"))
+    O_ref, L_ref = esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos, softmax_scale=pc.scale, workspace=ws)
+    torch.cuda.synchronize()
+    assert not torch.isnan(O_ref.float()).any() and not torch.isnan(L_ref).any()
+    O_g, L_g = nan_like(O_ref), nan_like(L_ref)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                                  # warm-up on the capture's side stream, as torch asks
+        esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos, softmax_scale=pc.scale, O=O_g, LSE=L_g, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos, softmax_scale=pc.scale, O=O_g, LSE=L_g, workspace=ws)
+    for rep in range(4):
+        say(f"graph replay {rep}")
+        O_g.copy_(nan_like(O_g)); L_g.copy_(nan_like(L_g))
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(O_g.view(torch.int16), O_ref.view(torch.int16)) and torch.equal(L_g.view(torch.int32), L_ref.view(torch.int32)), f"replay {rep}"
+        if rep % 2 == 0:                                           # an eager call in between, same workspace
+            O_e, L_e = esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos, softmax_scale=pc.scale, workspace=ws)
+            torch.cuda.synchronize()
+            assert torch.equal(O_e.view(torch.int16), O_ref.view(torch.int16))
+
+
+@pytest.mark.gpu
 @pytest.mark.parametrize("seed", list(range(10)))
 def test_prefill_randomized_layouts(esp, cuda, seed):
     """Seeded random layouts: head counts, batch, ragged lengths up to several query tiles and a dozen KV tiles,
