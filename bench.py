@@ -251,6 +251,10 @@ def main():
     def avg(i, j):
         return sum(e[i].elapsed_time(e[j]) for e in recs) / len(recs)   # ms
 
+    def spread(i, j):
+        v = sorted(e[i].elapsed_time(e[j]) for e in recs)
+        return {"min": v[0], "median": v[len(v) // 2], "max": v[-1]}
+
     ms_prefill = avg(0, 1)
     ms_merge = avg(1, 2) if len(pc.shards) > 1 else 0.0
     flops = pc.flops()
@@ -263,7 +267,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": name, "Hq": pc.Hq, "Hkv": pc.Hkv, "head_dim": pc.D, "prefill_Tq": pc.Tq,
                    "prefill_shards": n_calls, "prefill_flops": flops},
-        "prefill": {"ms_all_shards": ms_prefill, "ms_per_shard_call": ms_prefill / n_calls, "ms_merge": ms_merge,
+        "prefill": {"ms_all_shards": ms_prefill, "ms_all_shards_spread": spread(0, 1), "ms_per_shard_call": ms_prefill / n_calls, "ms_merge": ms_merge,
                     "tflops": tflops, "pct_of_peak": 100.0 * tflops / PEAK_BF16_TFLOPS},
         "roofline": {"kernel": "prefill_kernel", "bound": "mfma", "achieved": tflops, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS, "traffic": None,
@@ -321,6 +325,58 @@ def main():
         result["retain"] = {"ms_prefill_alone": t_plain, "ms_prefill_with_retention": t_ret,
                             "overhead_pct": 100.0 * (t_ret / t_plain - 1.0), "rows_retained": n_rows,
                             "bytes_moved": 2 * 2 * n_rows * pc.Hkv * pc.D * 2, "pool_matches": bool(ok)}
+    if "decode" in result:
+        result["decode"]["ms_spread"] = spread(3, 4)
+    if args.workload == "lwm7b" and single and len(pc.shards) > 1:
+        # the same keys in one call: the shards concatenated and put in order of position (any order of rows is a
+        # valid shard; ascending positions are what lets whole tiles be skipped or left unmasked)
+        p_all = torch.cat([s.kv_pos for s in pc.shards])
+        order = torch.argsort(p_all)
+        k_all = torch.cat([s.k for s in pc.shards])[order].contiguous(); v_all = torch.cat([s.v for s in pc.shards])[order].contiguous()
+        p_all = p_all[order].contiguous()
+        ws1 = torch.empty(esp.esp_prefill_workspace_bytes(pc.Tq, k_all.shape[0], 1, pc.Hq, pc.Hkv, pc.D), dtype=torch.uint8, device=dev)
+        one = lambda: esp.esp_partial_attn_prefill(pc.q, k_all, v_all, pc.q_pos, p_all, softmax_scale=pc.scale, causal=pc.causal,
+                                                   O=out_O, LSE=out_L, workspace=ws1)
+        one(); torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(max(3, args.steps // 2)):
+            one()
+        e1.record(); torch.cuda.synchronize()
+        ms_one = e0.elapsed_time(e1) / max(3, args.steps // 2)
+        result["prefill"]["one_call_over_all_shards"] = {"ms": ms_one, "tflops": flops / (ms_one * 1e-3) / 1e12,
+                                                          "note": "the four shards as one shard of 32768 rows in order of position"}
+        del k_all, v_all
+    # what a bare loop sustains on this box, for "fraction of achievable" beside "fraction of the published peak"
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    gen = torch.Generator(device=dev).manual_seed(7)
+    ops_n = torch.randn(1 << 16, generator=gen, device=dev).to(torch.bfloat16)
+    probe = {}
+    for label, ops in (("normal", ops_n), ("constant", torch.full_like(ops_n, 1.0))):
+        best = None
+        for _ in range(4):
+            e0, e1 = ev(), ev()
+            e0.record()
+            fl = esp.esp_probe_mfma_bf16(ops, 20000, sink)
+            e1.record(); torch.cuda.synchronize()
+            t = e0.elapsed_time(e1)
+            best = t if best is None else min(best, t)
+        probe["mfma_bf16_tflops_%s_operands" % label] = fl / (best * 1e-3) / 1e12
+    buf = torch.empty(1 << 30, dtype=torch.int32, device=dev).fill_(1)       # 4 GiB, far beyond the last-level cache
+    best = None
+    for _ in range(4):
+        e0, e1 = ev(), ev()
+        e0.record()
+        nb = esp.esp_probe_stream_read(buf, sink)
+        e1.record(); torch.cuda.synchronize()
+        t = e0.elapsed_time(e1)
+        best = t if best is None else min(best, t)
+    probe["hbm_read_gbs"] = nb / (best * 1e-3) / 1e9
+    del buf
+    result["achievable"] = probe
+    result["roofline"]["frac_of_bare_mfma_loop_normal_operands"] = tflops / probe["mfma_bf16_tflops_normal_operands"]
+    if "roofline_decode" in result:
+        result["roofline_decode"]["frac_of_streaming_read"] = result["decode"]["gbs"] / probe["hbm_read_gbs"]
     if args.multi_master and dc is not None and dc.B >= 2:
         # Sec. 4.2 / Fig. 8: every instance is master of some requests (it has their queries) and a helper for the
         # rest, whose queries come from their masters and whose partial results go back to them

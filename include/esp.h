@@ -180,6 +180,21 @@ size_t esp_prefill_pool_workspace_bytes(int32_t Tq, int32_t Tkv, int32_t batch,
                                         int32_t Hq, int32_t Hkv, int32_t D);
 
 /*
+ * Measurement aids (no part of the method): what this GPU sustains on the two
+ * resources that bound the path, for the benchmark's "achievable" figures.
+ *   esp_probe_mfma_bf16: every wavefront (8 per CU, all CUs) runs `iters` rounds of
+ *     four independent 32x32x16 bf16 MFMAs on register operands taken from
+ *     `operands` (device, 16-byte aligned, operand_bytes a multiple of 16; the
+ *     values decide how much the multipliers switch, hence the clock under the
+ *     power limit).  *flops (host, nullable) receives the FLOPs of the launch.
+ *   esp_probe_stream_read: reads `bytes` (a multiple of 16) of device memory once.
+ *   sink: 4 bytes of device memory (written only in a case that does not occur).
+ */
+esp_status esp_probe_mfma_bf16(const void* operands, int64_t operand_bytes, int32_t iters,
+                               void* sink, int64_t* flops, void* stream);
+esp_status esp_probe_stream_read(const void* src, int64_t bytes, void* sink, void* stream);
+
+/*
  * Prefill batching plan (Sec. 5.4 "Batching", the dynamic program over sorted requests and sorted elastic
  * instances) -- host code, no GPU work; every pointer is HOST memory.
  *

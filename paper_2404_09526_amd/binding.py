@@ -23,6 +23,7 @@ EXPORTS = (
     "esp_decode_workspace_bytes", "esp_merge_partials", "esp_kv_append", "esp_last_error", "esp_version",
     "esp_plan_prefill_batches", "esp_fit_prefill_model",
     "esp_kv_gather", "esp_partial_attn_prefill_pool", "esp_prefill_pool_workspace_bytes",
+    "esp_probe_mfma_bf16", "esp_probe_stream_read",
 )
 
 
@@ -57,6 +58,10 @@ def _load() -> ctypes.CDLL:
     L.esp_partial_attn_prefill_pool.restype = i32
     L.esp_prefill_pool_workspace_bytes.argtypes = [i32] * 6
     L.esp_prefill_pool_workspace_bytes.restype = sz
+    L.esp_probe_mfma_bf16.argtypes = [vp, i64, i32, vp, vp, vp]
+    L.esp_probe_mfma_bf16.restype = i32
+    L.esp_probe_stream_read.argtypes = [vp, i64, vp, vp]
+    L.esp_probe_stream_read.restype = i32
     L.esp_plan_prefill_batches.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp]
     L.esp_plan_prefill_batches.restype = i32
     L.esp_fit_prefill_model.argtypes = [vp, vp, vp, vp, i32, vp]
@@ -273,6 +278,24 @@ def esp_partial_attn_prefill_pool(q, k_pool, v_pool, slot_idx, q_pos, kv_pos, cu
                                              float(softmax_scale), 1 if causal else 0, _ptr(O), _ptr(LSE), _ptr(workspace),
                                              workspace.numel(), _stream()))
     return O, LSE
+
+
+def esp_probe_mfma_bf16(operands, iters, sink) -> int:
+    """Launches the bare MFMA loop on register operands taken from `operands` (bf16); returns the FLOPs of the launch."""
+    _dev(operands, torch.bfloat16, "operands"); _dev(sink, torch.float32, "sink")
+    flops = ctypes.c_int64(0)
+    _check(lib.esp_probe_mfma_bf16(_ptr(operands), operands.numel() * 2, int(iters), _ptr(sink), ctypes.byref(flops), _stream()))
+    return int(flops.value)
+
+
+def esp_probe_stream_read(src, sink) -> int:
+    """Launches one streaming read of `src` (any dtype, contiguous); returns the bytes read."""
+    if not src.is_cuda or not src.is_contiguous():
+        raise ValueError("probe: src must be a contiguous device tensor")
+    _dev(sink, torch.float32, "sink")
+    nbytes = src.numel() * src.element_size()
+    _check(lib.esp_probe_stream_read(_ptr(src), nbytes, _ptr(sink), _stream()))
+    return nbytes
 
 
 def esp_plan_prefill_batches(req_len, free_slots, coefs, with_tables=False):

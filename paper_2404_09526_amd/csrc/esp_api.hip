@@ -72,6 +72,19 @@ esp_status esp_partial_attn_prefill(const void* q, const void* k, const void* v,
                           softmax_scale, causal, O, LSE, workspace, workspace_bytes, (hipStream_t)stream);
 }
 
+esp_status esp_probe_mfma_bf16(const void* operands, int64_t operand_bytes, int32_t iters, void* sink, int64_t* flops,
+                               void* stream) {
+    if (!operands || operand_bytes < 16 || (operand_bytes & 15) || ((uintptr_t)operands & 15) || iters < 1 || !sink)
+        return fail(ESP_ERR_INVALID_ARG, "probe: operands (16-byte aligned, a multiple of 16 bytes), iters >= 1 and a sink are needed");
+    return launch_probe_mfma(operands, operand_bytes, iters, sink, flops, (hipStream_t)stream);
+}
+
+esp_status esp_probe_stream_read(const void* src, int64_t bytes, void* sink, void* stream) {
+    if (!src || bytes < 16 || (bytes & 15) || ((uintptr_t)src & 15) || !sink)
+        return fail(ESP_ERR_INVALID_ARG, "probe: a 16-byte aligned buffer of a multiple of 16 bytes and a sink are needed");
+    return launch_probe_read(src, bytes, sink, (hipStream_t)stream);
+}
+
 esp_status esp_kv_gather(const void* k_pool, const void* v_pool, const int32_t* slot_idx, int32_t T, int64_t num_slots,
                          int32_t Hkv, int32_t D, void* k, void* v, void* stream) {
     if (T < 0 || num_slots < 0 || Hkv <= 0) return fail(ESP_ERR_INVALID_ARG, "gather: negative size");

@@ -44,6 +44,9 @@ esp_status launch_kv_append(const void* k, const void* v, const int32_t* slot_id
                             void* v_pool, int32_t row_bytes, hipStream_t stream);
 esp_status launch_kv_gather(const void* k_pool, const void* v_pool, const int32_t* slot_idx, int32_t T, int64_t num_slots,
                             void* k, void* v, int32_t row_bytes, hipStream_t stream);
+esp_status launch_probe_mfma(const void* operands, int64_t operand_bytes, int32_t iters, void* sink, int64_t* flops,
+                             hipStream_t stream);
+esp_status launch_probe_read(const void* src, int64_t bytes, void* sink, hipStream_t stream);
 esp_status launch_merge(const MergeArgs& parts, int32_t P, int64_t pairs, void* O, float* LSE_out,
                         hipStream_t stream);
 

@@ -767,13 +767,16 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         const int pool_items = M > S * L ? (M - S * L) * (split ? 8 : 1) : 0;
         int i_pool = 0;
         bool drew = false;
+        long long item_started = 0;
         for (int s = 0;; ++s) {
             // Long requests: the workgroups of an XCD that share a KV head (the same ones in every dealt round) walk
             // K/V together, and the L2 serves all but the first of them, as long as they stay within the few dozen
             // tiles it can hold per head.  Their items differ in length, so they would start the next round up to
             // that far apart, and since all run at the same speed the gap never closes: K/V then comes from memory
             // several times over.  So they wait for each other at the start of a dealt round: an arrival count per
-            // (XCD, KV head), tagged like the pool counter, and a wait that ends by itself after kSyncTicks.
+            // (XCD, KV head), tagged like the pool counter, and a wait that ends by itself: after 1/64 of the time
+            // this workgroup's previous item took (waiting pays only where the items are long and alike; where they
+            // differ a lot, as in a triangular sweep, it must cost next to nothing), at most after kSyncTicks.
             if (a.group_sync && s >= 1 && (s + 1) * L <= M && tid == 0) {
                 const int m_next = s * L + ((s & 1) ? L - 1 - l : l);
                 unsigned long long* ctr = a.pool + 2 + x * width + (m_next % width) / G;
@@ -781,11 +784,12 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
                 const int before_me = draw_finish(ctr, __hip_atomic_fetch_add(ctr, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
                 if ((uint32_t)before_me + 1 < target) {
                     const long long t0 = wall_clock64();
+                    const long long patience = min(kSyncTicks, (t0 - item_started) >> 6);
                     for (;;) {
                         const unsigned long long cur = __hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         // a count that is no longer this launch's was cleared by the last arrival (see below)
                         if ((uint32_t)(cur >> 32) != a.tag || (uint32_t)cur >= target) break;
-                        if (wall_clock64() - t0 > kSyncTicks) break;
+                        if (wall_clock64() - t0 > patience) break;
                         __builtin_amdgcn_s_sleep(16);
                     }
                 } else if ((s + 2) * L > M) {
@@ -811,6 +815,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
             }
             if (m >= M) break;                                        // only when M <= L: fewer items than workgroups
             unsigned long long* claim = (s >= S - 1 && pool_items > 0) ? a.pool : nullptr;
+            if (a.group_sync) item_started = wall_clock64();
             const bool ran = process(m / width, qu * width + m % width, claim);
             drew = claim != nullptr;
             if (drew && !ran) {                                       // no such query tile: it drew nothing
@@ -844,9 +849,12 @@ esp_status launch_prefill(const void* q, const void* k, const void* v, const int
     const unsigned grid = (unsigned)(items < cus ? items : cus);
     a.pool = (unsigned long long*)workspace;
     a.tag = next_launch_tag();
-    // start-of-round waits: one request with at least 512 KV tiles, XCD split, the same number of workgroups on
-    // every KV head of an XCD; the counters ((XCD, KV head), at most 8 x heads_per_xcd) follow the pool counter
-    a.group_sync = (a.heads_per_xcd > 0 && batch == 1 && Tkv >= 512 * kBN && (cus / 8) % a.heads_per_xcd == 0 &&
+    // start-of-round waits: one request with at least 512 KV tiles and a query chunk of at most an eighth of them
+    // (a chunk against a long prefix: every query tile then sees nearly all of the shard, the items are alike), XCD
+    // split, the same number of workgroups on every KV head of an XCD; the counters ((XCD, KV head), at most
+    // 8 x heads_per_xcd) follow the pool counter
+    a.group_sync = (a.heads_per_xcd > 0 && batch == 1 && Tkv >= 512 * kBN && (int64_t)Tkv >= 8 * (int64_t)Tq &&
+                    (cus / 8) % a.heads_per_xcd == 0 &&
                     8 * (2 + 8 * (size_t)a.heads_per_xcd) <= workspace_bytes) ? 1 : 0;
     hipLaunchKernelGGL(prefill_kernel, dim3(grid), dim3(kPfWaves * 64), 0, stream, a);
     return check_launch("prefill_kernel");
