@@ -29,7 +29,13 @@
  *     failed.  esp_last_error() gives a thread-local message.
  *   - The CONTENT of device index arrays (positions, offsets, slots) is
  *     trusted, as it comes from the scheduler (scaling plan, Sec. 3 and 4.1):
- *     out-of-range or duplicate slots are undefined behaviour.
+ *     out-of-range or duplicate slots are undefined behaviour.  With
+ *     ESP_DEBUG_VALIDATE=1 in the environment the calls check them first, on
+ *     the host (the stream is waited for and the arrays are copied back; a
+ *     debugging aid): prefix offsets must run from 0 to the row count without
+ *     decreasing, with no piece above the stated maximum; decode slots must lie
+ *     in [0, num_slots); append slots must be below num_slots and, where not
+ *     negative, distinct.  A violation returns ESP_ERR_INVALID_ARG.
  *   - A row with no visible key yields O = 0 and LSE = -inf, never NaN.
  *   - LSE is the natural logarithm of the sum of exp(softmax_scale * q.k)
  *     over the visible keys.

@@ -2,6 +2,11 @@
 // Every step of the hot path runs in the HIP kernels of this library; there is no fallback.
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <algorithm>
+#include <vector>
 
 #include "esp_common.h"
 
@@ -24,6 +29,46 @@ esp_status check_launch(const char* what) {
 }
 
 static bool heads_ok(int32_t Hq, int32_t Hkv) { return Hq > 0 && Hkv > 0 && Hq % Hkv == 0; }
+
+// ESP_DEBUG_VALIDATE=1 in the environment: the content of the device index arrays, trusted otherwise, is checked on
+// the host before the launch.  A debugging aid: it waits for the stream and copies the arrays back.
+static bool debug_validate() {
+    const char* e = getenv("ESP_DEBUG_VALIDATE");
+    return e && strcmp(e, "0") != 0 && e[0] != 0;
+}
+static bool fetch_i32(const int32_t* dev, size_t n, hipStream_t stream, std::vector<int32_t>& out) {
+    out.resize(n);
+    if (n == 0) return true;
+    if (hipStreamSynchronize(stream) != hipSuccess) return false;
+    return hipMemcpy(out.data(), dev, n * sizeof(int32_t), hipMemcpyDeviceToHost) == hipSuccess;
+}
+// prefix offsets: start at 0, never decrease, end at `total`, no piece longer than `longest`
+static esp_status check_offsets(const char* what, const int32_t* dev, int32_t n, int64_t total, int64_t longest, hipStream_t stream) {
+    std::vector<int32_t> h;
+    if (!fetch_i32(dev, (size_t)n + 1, stream, h)) return fail(ESP_ERR_HIP, "%s: cannot read the offsets back", what);
+    if (h[0] != 0 || h[n] != total) return fail(ESP_ERR_INVALID_ARG, "%s: offsets run from %d to %d, expected 0 to %lld", what, h[0], h[n], (long long)total);
+    for (int32_t i = 0; i < n; ++i) {
+        if (h[i + 1] < h[i]) return fail(ESP_ERR_INVALID_ARG, "%s: offsets decrease at entry %d", what, i + 1);
+        if ((int64_t)h[i + 1] - h[i] > longest) return fail(ESP_ERR_INVALID_ARG, "%s: piece %d has %d rows, more than the stated maximum %lld", what, i, h[i + 1] - h[i], (long long)longest);
+    }
+    return ESP_OK;
+}
+// slots: below num_slots; negative ones only where the call gives them a meaning; no slot twice if asked
+static esp_status check_slots(const char* what, const int32_t* dev, int64_t n, int64_t num_slots, bool negative_ok, bool unique,
+                              hipStream_t stream) {
+    std::vector<int32_t> h;
+    if (!fetch_i32(dev, (size_t)n, stream, h)) return fail(ESP_ERR_HIP, "%s: cannot read the slots back", what);
+    for (int64_t i = 0; i < n; ++i) {
+        if (h[i] >= num_slots) return fail(ESP_ERR_INVALID_ARG, "%s: slot_idx[%lld] = %d is not below num_slots = %lld", what, (long long)i, h[i], (long long)num_slots);
+        if (h[i] < 0 && !negative_ok) return fail(ESP_ERR_INVALID_ARG, "%s: slot_idx[%lld] = %d is negative", what, (long long)i, h[i]);
+    }
+    if (unique) {
+        std::sort(h.begin(), h.end());
+        for (int64_t i = 1; i < n; ++i)
+            if (h[i] >= 0 && h[i] == h[i - 1]) return fail(ESP_ERR_INVALID_ARG, "%s: slot %d is named twice", what, h[i]);
+    }
+    return ESP_OK;
+}
 
 }  // namespace esp
 
@@ -68,6 +113,11 @@ esp_status esp_partial_attn_prefill(const void* q, const void* k, const void* v,
     if (need > 0 && (!workspace || workspace_bytes < need))
         return fail(ESP_ERR_WORKSPACE, "prefill: workspace needs %zu bytes, got %zu", need, workspace ? workspace_bytes : (size_t)0);
     if (need > 0 && ((uintptr_t)workspace & 255)) return fail(ESP_ERR_WORKSPACE, "prefill: workspace not 256-byte aligned");
+    if (cu_q && debug_validate()) {
+        esp_status st = check_offsets("prefill: cu_q", cu_q, batch, Tq, max_q, (hipStream_t)stream);
+        if (st == ESP_OK) st = check_offsets("prefill: cu_kv", cu_kv, batch, Tkv, max_kv, (hipStream_t)stream);
+        if (st != ESP_OK) return st;
+    }
     return launch_prefill(q, k, v, q_pos, kv_pos, cu_q, cu_kv, batch, Tq, Tkv, max_q, max_kv, Hq, Hkv,
                           softmax_scale, causal, O, LSE, workspace, workspace_bytes, (hipStream_t)stream);
 }
@@ -150,6 +200,11 @@ esp_status esp_partial_attn_decode(const void* q, const void* k_pool, const void
     if (!workspace || workspace_bytes < need)
         return fail(ESP_ERR_WORKSPACE, "decode: workspace needs %zu bytes, got %zu", need, workspace ? workspace_bytes : (size_t)0);
     if ((uintptr_t)workspace & 255) return fail(ESP_ERR_WORKSPACE, "decode: workspace not 256-byte aligned");
+    if (debug_validate()) {
+        esp_status st = check_offsets("decode: seq_offsets", seq_offsets, B, total_tokens, max_len, (hipStream_t)stream);
+        if (st == ESP_OK) st = check_slots("decode", slot_idx, total_tokens, num_slots, false, false, (hipStream_t)stream);
+        if (st != ESP_OK) return st;
+    }
     return launch_decode(q, k_pool, v_pool, slot_idx, seq_offsets, B, total_tokens, Hq, Hkv, softmax_scale, O, LSE,
                          workspace, workspace_bytes, (hipStream_t)stream);
 }
@@ -179,6 +234,10 @@ esp_status esp_kv_append(const void* k, const void* v, const int32_t* slot_idx, 
     if (T == 0) return ESP_OK;
     if (!k || !v || !slot_idx || !k_pool || !v_pool) return fail(ESP_ERR_INVALID_ARG, "append: null pointer");
     if (num_slots == 0) return fail(ESP_ERR_INVALID_ARG, "append: empty pool");
+    if (debug_validate()) {
+        esp_status st = check_slots("append", slot_idx, T, num_slots, true, true, (hipStream_t)stream);
+        if (st != ESP_OK) return st;
+    }
     return launch_kv_append(k, v, slot_idx, T, k_pool, v_pool, Hkv * D * 2, (hipStream_t)stream);
 }
 

@@ -338,6 +338,52 @@ def test_prefill_more_items_than_workgroups(esp, cuda, Hq, Hkv):
     run_prefill_case(esp, pc)
 
 
+def test_debug_validation_of_index_arrays(esp, cuda, monkeypatch):
+    """ESP_DEBUG_VALIDATE=1: slots outside the pool, slots named twice, offsets that decrease or do not end at the row
+    count are refused with ESP_ERR_INVALID_ARG before anything is launched; sound arrays pass and give the usual result."""
+    monkeypatch.setenv("ESP_DEBUG_VALIDATE", "1")
+    dc = wl.config1_decode(cuda)
+    max_len = int(dc.lens.max())
+    O, L = esp.esp_partial_attn_decode(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, max_len, softmax_scale=dc.scale)
+    bad = dc.slot_idx.clone(); bad[17] = dc.num_slots
+    with pytest.raises(esp.EspError) as e:
+        esp.esp_partial_attn_decode(dc.q, dc.k_pool, dc.v_pool, bad, dc.seq_offsets, max_len, softmax_scale=dc.scale)
+    assert e.value.status == -1 and "slot_idx[17]" in str(e.value)
+    bad = dc.slot_idx.clone(); bad[3] = -1
+    with pytest.raises(esp.EspError):
+        esp.esp_partial_attn_decode(dc.q, dc.k_pool, dc.v_pool, bad, dc.seq_offsets, max_len, softmax_scale=dc.scale)
+    off = dc.seq_offsets.clone(); off[2] = off[1] - 1
+    with pytest.raises(esp.EspError) as e:
+        esp.esp_partial_attn_decode(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, off, max_len, softmax_scale=dc.scale)
+    assert "decrease" in str(e.value)
+    with pytest.raises(esp.EspError):                              # a request longer than the stated maximum
+        esp.esp_partial_attn_decode(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, max_len - 1, softmax_scale=dc.scale)
+    # append: distinct non-negative slots below the pool size; negative ones mean "not kept"
+    kp, vp = dc.k_pool.clone(), dc.v_pool.clone()
+    twice = dc.new_slots.clone(); twice[1] = twice[0]
+    with pytest.raises(esp.EspError) as e:
+        esp.esp_kv_append(dc.new_k, dc.new_v, twice, kp, vp)
+    assert "twice" in str(e.value)
+    high = dc.new_slots.clone(); high[0] = dc.num_slots + 5
+    with pytest.raises(esp.EspError):
+        esp.esp_kv_append(dc.new_k, dc.new_v, high, kp, vp)
+    assert torch.equal(kp, dc.k_pool) and torch.equal(vp, dc.v_pool)      # nothing was written by the refused calls
+    skipped = dc.new_slots.clone(); skipped[:2] = -1
+    esp.esp_kv_append(dc.new_k, dc.new_v, skipped, kp, vp)
+    # prefill: offsets of a var-len batch
+    pc = wl.striped_prefill("validate", [70, 130], 2, 0, 4, 4, 90, cuda)
+    s0 = pc.shards[0]
+    esp.esp_partial_attn_prefill(pc.q, s0.k, s0.v, pc.q_pos, s0.kv_pos, pc.cu_q, s0.cu_kv, pc.max_q, s0.max_kv, softmax_scale=pc.scale)
+    short = s0.cu_kv.clone(); short[-1] -= 1
+    with pytest.raises(esp.EspError):
+        esp.esp_partial_attn_prefill(pc.q, s0.k, s0.v, pc.q_pos, s0.kv_pos, pc.cu_q, short, pc.max_q, s0.max_kv, softmax_scale=pc.scale)
+    torch.cuda.synchronize()
+    monkeypatch.delenv("ESP_DEBUG_VALIDATE")
+    O2, L2 = esp.esp_partial_attn_decode(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, max_len, softmax_scale=dc.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(O, O2) and torch.equal(L, L2)
+
+
 def pool_image(rng, shard, num_slots):
     """Host pool arrays holding the shard's rows at random distinct slots (built by the oracle's own scatter), plus noise
     in every other slot; returns (k_pool, v_pool, slots) as numpy arrays."""
