@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--retain", action="store_true",
                     help="proactive retention (scale-down during prefill): while each shard is attended, esp_kv_append keeps "
                          "ALL its rows in a token pool from a second stream; reports the overhead against prefill alone")
+    ap.add_argument("--one-call", action="store_true",
+                    help="also time one prefill call over all shards put together in order of position (not part of the default "
+                         "run, so that the kernel statistics of a profiled default run hold launches of one shape only)")
     ap.add_argument("--multi-master", action="store_true",
                     help="distributed decoding with several masters on one GPU: this instance decodes the requests it is master "
                          "of while the queries of the other masters' requests arrive (host-to-device copies on a second stream), "
@@ -327,7 +330,7 @@ def main():
                             "bytes_moved": 2 * 2 * n_rows * pc.Hkv * pc.D * 2, "pool_matches": bool(ok)}
     if "decode" in result:
         result["decode"]["ms_spread"] = spread(3, 4)
-    if args.workload == "lwm7b" and single and len(pc.shards) > 1:
+    if args.one_call and single and len(pc.shards) > 1:
         # the same keys in one call: the shards concatenated and put in order of position (any order of rows is a
         # valid shard; ascending positions are what lets whole tiles be skipped or left unmasked)
         p_all = torch.cat([s.kv_pos for s in pc.shards])
