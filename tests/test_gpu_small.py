@@ -465,6 +465,33 @@ def test_prefill_workspace_contents_do_not_matter(esp, cuda, fill):
 
 
 @pytest.mark.gpu
+def test_prefill_calls_on_two_streams_with_a_workspace_each(esp, cuda):
+    """Two calls that may run at the same time (two streams of default priority), each with its own workspace, as the
+    header asks: both must give what they give alone (bit for bit; the single calls are checked against the oracle by
+    the other tests).  More items than workgroups in both, so that both use their item pool."""
+    cases = []
+    for k, (Tq, Hq, Hkv) in enumerate([(256 * 40 + 7, 8, 8), (256 * 36 + 100, 16, 8)]):
+        pc = wl.contiguous_prefill(f"two-streams-{k}", Tq, 150, [(0, 400)], Hq, Hkv, 81 + k, cuda)
+        pc.q_pos[:] = torch.randint(0, 800, (Tq,), dtype=torch.int32, device=cuda)
+        s = pc.shards[0]
+        O_ref, L_ref = esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos, softmax_scale=pc.scale)
+        ws = torch.empty(esp.esp_prefill_workspace_bytes(Tq, 400, 1, Hq, Hkv, 128), dtype=torch.uint8, device=cuda)
+        cases.append((pc, s, O_ref, L_ref, ws, torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    for rep in range(3):
+        outs = []
+        for pc, s, O_ref, L_ref, ws, st in cases:
+            O = torch.full_like(O_ref, float("nan")); L = torch.full_like(L_ref, float("nan"))
+            st.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(st):
+                esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos, softmax_scale=pc.scale, O=O, LSE=L, workspace=ws)
+            outs.append((O, L))
+        torch.cuda.synchronize()
+        for (pc, s, O_ref, L_ref, ws, st), (O, L) in zip(cases, outs):
+            assert torch.equal(O.view(torch.int16), O_ref.view(torch.int16)) and torch.equal(L.view(torch.int32), L_ref.view(torch.int32)), (pc.name, rep)
+
+
+@pytest.mark.gpu
 def test_prefill_replayed_from_a_captured_graph(esp, cuda):
     """A prefill call recorded into a graph and replayed: the replays carry the recorded launch's arguments, counters'
     tag included, and must still work every item exactly once.  Replays alternate with eager calls on the same
