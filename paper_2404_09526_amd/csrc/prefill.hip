@@ -32,6 +32,7 @@
 //     the others apply the element-wise test kv_pos <= q_pos; past the last tile any of its own
 //     rows can see a wavefront stops its arithmetic and only keeps up transfers and barriers.
 #include <limits.h>
+#include <stdlib.h>
 
 #include <atomic>
 #include <chrono>
@@ -83,6 +84,7 @@ struct PrefillArgs {
     unsigned long long* pool;         // counter of the item pool: launch tag (high word), draws so far (low word)
     uint32_t tag;                     // this launch's tag
     int32_t group_sync;               // workgroups sharing a KV head start their dealt rounds together
+    int32_t sync_ticks;               // longest such wait, in ticks of the 100 MHz wall clock
     float scale_log2;
 };
 
@@ -784,7 +786,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
                 const int before_me = draw_finish(ctr, __hip_atomic_fetch_add(ctr, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
                 if ((uint32_t)before_me + 1 < target) {
                     const long long t0 = wall_clock64();
-                    const long long patience = min(kSyncTicks, (t0 - item_started) >> 6);
+                    const long long patience = min((long long)a.sync_ticks, (t0 - item_started) >> 6);
                     for (;;) {
                         const unsigned long long cur = __hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         // a count that is no longer this launch's was cleared by the last arrival (see below)
@@ -856,6 +858,13 @@ esp_status launch_prefill(const void* q, const void* k, const void* v, const int
     a.group_sync = (a.heads_per_xcd > 0 && batch == 1 && Tkv >= 512 * kBN && (int64_t)Tkv >= 8 * (int64_t)Tq &&
                     (cus / 8) % a.heads_per_xcd == 0 &&
                     8 * (2 + 8 * (size_t)a.heads_per_xcd) <= workspace_bytes) ? 1 : 0;
+    // ESP_PREFILL_SYNC_TICKS in the environment replaces the longest wait (0: every wait gives up at once; a test uses
+    // it to run the path a missing workgroup would take)
+    a.sync_ticks = (int32_t)kSyncTicks;
+    if (const char* e = getenv("ESP_PREFILL_SYNC_TICKS")) {
+        const long v = strtol(e, nullptr, 10);
+        if (v >= 0 && v <= 1000000) a.sync_ticks = (int32_t)v;
+    }
     hipLaunchKernelGGL(prefill_kernel, dim3(grid), dim3(kPfWaves * 64), 0, stream, a);
     return check_launch("prefill_kernel");
 }

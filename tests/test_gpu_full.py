@@ -85,6 +85,17 @@ def test_config4_prefill_long_context(esp, cuda):
     check_prefill_sampled(esp, pc, 8, 104)
 
 
+@pytest.mark.parametrize("ticks", [None, "0"])
+def test_chunk_against_a_long_prefix_with_round_start_waits(esp, cuda, monkeypatch, ticks):
+    """A 4096-token chunk against 32768 earlier tokens: long, alike items, so the workgroups that share a KV head wait
+    for each other at the start of every dealt round.  Run as is, and with the longest wait set to nothing, so that
+    every wait gives up at once (what a missing workgroup causes): the results must not depend on it."""
+    if ticks is not None:
+        monkeypatch.setenv("ESP_PREFILL_SYNC_TICKS", ticks)
+    pc = wl.contiguous_prefill("chunk-vs-prefix", 4096, 32768 - 4096, [(0, 32768)], 32, 32, 33, cuda)
+    check_prefill_sampled(esp, pc, 96, 7)
+
+
 def test_config5_prefill_varlen_gqa(esp, cuda):
     pc = wl.config5_prefill(cuda)
     assert pc.visible_pairs_per_head == 2994661376
