@@ -12,7 +12,8 @@ Two independent statements live here:
   * ``brute_force_attention`` (dense score matrix in numpy), which exists only
     to pin the C routine on tiny inputs.
 Pinning status: every function below is pinned by tests/test_oracle_pins.py
-(brute force, a library attention routine, closed forms, partition and
+(brute force, also on every request's slice of a packed var-len shard through the
+per-sample key-row range; a library attention routine; closed forms; partition and
 permutation invariance).  The paper prints no numeric worked example, so no
 paper-printed value is among the pins.
 """

@@ -48,6 +48,57 @@ def test_matches_dense_brute_force(causal, Hq, Hkv, d):
     assert (O[~fin] == 0).all()
 
 
+# ------------------------------------------------------------------ P1b: the per-sample key-row range (var-len batches)
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (4, 2)])
+def test_row_range_of_a_packed_shard_matches_brute_force_on_each_slice(causal, Hq, Hkv):
+    """Several requests packed into one shard (one of them without any row, positions shuffled inside every
+    request): a sample that names its request's rows [kv_lo, kv_hi) must equal dense brute-force attention run on
+    that request's slice alone.  The requests overlap in position, every request's rows carry other positions
+    than the same indices counted from row 0, and the ranges end neither at the shard's end nor at a common
+    length, so a position read at the index within the range instead of the row, a range one row short or long,
+    or keys of a neighbouring request all change the result."""
+    rng = np.random.default_rng(77 + Hq + Hkv)
+    q_lens, kv_lens = [5, 3, 9, 4], [17, 0, 41, 8]
+    cu_q = np.concatenate([[0], np.cumsum(q_lens)]); cu_kv = np.concatenate([[0], np.cumsum(kv_lens)])
+    Tq, Tkv = int(cu_q[-1]), int(cu_kv[-1])
+    q = rand_bits(rng, (Tq, Hq, D)); k = rand_bits(rng, (Tkv, Hkv, D)); v = rand_bits(rng, (Tkv, Hkv, D))
+    qp = np.zeros(Tq, np.int32); kp = np.zeros(Tkv, np.int32)
+    for r in range(4):
+        # positions of request r: a shuffled draw from its own window; the windows of different requests overlap
+        allpos = (rng.permutation(80)[: q_lens[r] + kv_lens[r]] + 7 * r).astype(np.int32)
+        qp[cu_q[r]:cu_q[r + 1]] = allpos[: q_lens[r]]
+        kp[cu_kv[r]:cu_kv[r + 1]] = allpos[q_lens[r]:]
+    qp[cu_q[2]] = kp[cu_kv[2]:cu_kv[3]].min() - 1                      # a row of request 2 that sees none of its keys
+    rows = np.repeat(np.arange(Tq, dtype=np.int64), Hq); heads = np.tile(np.arange(Hq, dtype=np.int64), Tq)
+    req = np.searchsorted(cu_q, rows, side="right") - 1
+    scale = 0.13
+    O, L = oracle.partial_attn(q, k, v, qp, kp, scale, causal, rows, heads, cu_kv[req], cu_kv[req + 1])
+    O, L = O.reshape(Tq, Hq, D), L.reshape(Tq, Hq)
+    for r in range(4):
+        qs, ks = slice(cu_q[r], cu_q[r + 1]), slice(cu_kv[r], cu_kv[r + 1])
+        if kv_lens[r] == 0:
+            assert np.isneginf(L[qs]).all() and (O[qs] == 0).all()
+            continue
+        Ob, Lb = oracle.brute_force_attention(q[qs], k[ks], v[ks], qp[qs], kp[ks], scale, causal)
+        assert np.array_equal(np.isinf(L[qs]), np.isinf(Lb))
+        fin = ~np.isinf(Lb)
+        np.testing.assert_allclose(L[qs][fin], Lb[fin], rtol=0, atol=1e-12)
+        np.testing.assert_allclose(O[qs], Ob, rtol=0, atol=1e-12)
+    if causal:
+        assert np.isneginf(L[cu_q[2]]).all() and np.isfinite(L[cu_q[2] + 1:cu_q[3]]).any()
+    # a range that is a strict part of a request (the rows one instance holds of it), not starting at a request's start
+    lo, hi = cu_kv[2] + 5, cu_kv[3] - 7
+    n = q_lens[2] * Hq
+    r2 = np.repeat(np.arange(cu_q[2], cu_q[3], dtype=np.int64), Hq); h2 = np.tile(np.arange(Hq, dtype=np.int64), q_lens[2])
+    O2, L2 = oracle.partial_attn(q, k, v, qp, kp, scale, causal, r2, h2, np.full(n, lo), np.full(n, hi))
+    Ob, Lb = oracle.brute_force_attention(q[cu_q[2]:cu_q[3]], k[lo:hi], v[lo:hi], qp[cu_q[2]:cu_q[3]], kp[lo:hi], scale, causal)
+    fin = ~np.isinf(Lb)
+    assert np.array_equal(np.isinf(L2.reshape(-1, Hq)), np.isinf(Lb))
+    np.testing.assert_allclose(L2.reshape(-1, Hq)[fin], Lb[fin], rtol=0, atol=1e-12)
+    np.testing.assert_allclose(O2.reshape(-1, Hq, D), Ob, rtol=0, atol=1e-12)
+
+
 # ------------------------------------------------------------------ P2: library routine on a special case
 @pytest.mark.parametrize("Hq,Hkv", [(4, 4), (8, 2)])
 def test_matches_torch_sdpa_contiguous_causal(Hq, Hkv):
