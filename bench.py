@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--workload", default="lwm7b", choices=["lwm7b", "long", "mixed"],
                     help="lwm7b = configs[1]+configs[2] (default, the bench line); long = configs[3]; mixed = configs[4]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="skip the other full-size configurations that the default run times after its own steps "
+                         "(configs[3] and configs[4]; a profiled run then holds launches of the headline shapes only)")
     ap.add_argument("--retain", action="store_true",
                     help="proactive retention (scale-down during prefill): while each shard is attended, esp_kv_append keeps "
                          "ALL its rows in a token pool from a second stream; reports the overhead against prefill alone")
@@ -58,42 +61,35 @@ def parse():
 
 
 def cpu_baseline(pc, dc, wl, oracle):
-    """The oracle as it stands, timed on this host's cores on a bounded sample of the same workload."""
+    """The oracle as it stands, timed on this host's cores on a bounded sample of the same workload: for prefill
+    the very (row, head) samples the full-size parity test evaluates, against every shard."""
     import numpy as np
     out = {"kind": "oracle", "cores": oracle.num_threads()}
     sample = []
     if pc is not None:
-        rng = np.random.default_rng(0)
-        # about 10 s of fp64 work on 16 cores = 4e8 visible (query, key) pairs: 98304 (row, head) pairs on the
-        # default workload, fewer where a row sees more keys
-        pairs_per_row = max(1.0, pc.visible_pairs_per_head / len(pc.shards) / max(pc.Tq, 1))
-        n = int(min(98304, max(256, 4.0e8 / pairs_per_row)))
-        rows = rng.integers(0, pc.Tq, n).astype(np.int64)
-        heads = rng.integers(0, pc.Hq, n).astype(np.int64)
-        cu_q = wl.host_i32(pc.cu_q)
-        reqs = np.searchsorted(cu_q, rows, side="right") - 1
-        s = pc.shards[0]
-        cu_kv = wl.host_i32(s.cu_kv)
-        qb, kb, vb = wl.bits(pc.q), wl.bits(s.k), wl.bits(s.v)
-        qp, kp = wl.host_i32(pc.q_pos), wl.host_i32(s.kv_pos)
-        lo, hi = cu_kv[reqs], cu_kv[reqs + 1]
-        # visible pairs of the sample, to convert seconds into the metric's unit
-        pairs = 0
-        for r in range(pc.batch):
-            m = reqs == r
-            if m.any():
-                seg = np.sort(kp[cu_kv[r]:cu_kv[r + 1]])
-                pairs += int(np.searchsorted(seg, qp[rows[m]], side="right").sum()) if pc.causal else int(m.sum()) * len(seg)
-        t0 = time.perf_counter()
-        oracle.partial_attn(qb, kb, vb, qp, kp, pc.scale, pc.causal, rows, heads, lo, hi)
-        dt = time.perf_counter() - t0
+        n_total, seed = wl.PARITY_SAMPLES.get(pc.name, (1024, 0))
+        rows, heads, reqs = wl.prefill_parity_samples(pc, n_total, seed)
+        qb, qp = wl.bits(pc.q), wl.host_i32(pc.q_pos)
+        pairs, dt = 0, 0.0
+        for s in pc.shards:
+            cu_kv = wl.host_i32(s.cu_kv)
+            kb, vb, kp = wl.bits(s.k), wl.bits(s.v), wl.host_i32(s.kv_pos)
+            # visible pairs of the sample, to convert seconds into the metric's unit
+            for r in range(pc.batch):
+                m = reqs == r
+                if m.any():
+                    seg = np.sort(kp[cu_kv[r]:cu_kv[r + 1]])
+                    pairs += int(np.searchsorted(seg, qp[rows[m]], side="right").sum()) if pc.causal else int(m.sum()) * len(seg)
+            t0 = time.perf_counter()
+            oracle.partial_attn(qb, kb, vb, qp, kp, pc.scale, pc.causal, rows, heads, cu_kv[reqs], cu_kv[reqs + 1])
+            dt += time.perf_counter() - t0
         out["value"] = 4.0 * pc.D * pairs / dt / 1e12
         out["unit"] = "TFLOP/s"
         out["seconds"] = dt
-        sample.append(f"prefill: {n} random (row, head) pairs of shard 0 against the full shard ({pairs} visible pairs)")
+        sample.append(f"prefill: the {len(rows)} (row, head) samples of the full-size parity test against each of the "
+                      f"{len(pc.shards)} shards ({pairs} visible pairs)")
         out["extrapolated_full_prefill_s"] = dt * pc.visible_pairs_per_head * pc.Hq / max(pairs, 1)
     if dc is not None:
-        import numpy as np
         slots, off = wl.host_i32(dc.slot_idx), wl.host_i32(dc.seq_offsets)
         kpool = np.zeros((dc.num_slots, dc.Hkv, dc.D), np.uint16)
         vpool = np.zeros_like(kpool)
@@ -163,6 +159,117 @@ def note(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
+def make_workload(which, wl, np, dev):
+    """(prefill case, decode case, description) of one of the three benchmark workloads."""
+    pc = dc = None
+    if which == "lwm7b":
+        pc = wl.config2_prefill(dev)
+        lens = wl.lognormal_lengths(64, 8192, 1024, 131072, 2)
+        order = np.argsort(lens)
+        dc = wl.config3_decode(dev, sample_reqs=[int(i) for i in order[::4]])
+        name = "LWM-7B shape: prefill chunk 8192 x 4 striped shards of 8192 (configs[1]) + decode B=64 in a 4M-slot pool (configs[2])"
+    elif which == "long":
+        pc = wl.config4_prefill(dev)
+        name = "long-context prefill share: chunk 32768 against 262144 local KV (configs[3])"
+    else:
+        pc = wl.config5_prefill(dev)
+        lens = wl.lognormal_lengths(256, 16384, 512, 1 << 20, 4)
+        order = np.argsort(lens)
+        dc = wl.config5_decode(dev, sample_reqs=[int(order[0]), int(order[len(order) // 2])])
+        name = "mixed iteration: var-len GQA prefill of 6 requests x 4 striped shards + decode B=256 in a 16M-slot pool (configs[4])"
+    return pc, dc, name
+
+
+class Step:
+    """One pass of the hot path over a workload, with its buffers.  Partials of several shards stay on this GPU, so
+    they are written as fp32 and rounded to bf16 once, by the merge; a single shard's output is bf16 right away."""
+
+    def __init__(self, esp, torch, pc, dc, dev):
+        self.esp, self.torch, self.pc, self.dc = esp, torch, pc, dc
+        self.single = pc.batch == 1
+        several = len(pc.shards) > 1
+        self.ws_pf = torch.empty(max(esp.esp_prefill_workspace_bytes(pc.Tq, pc.shards[0].k.shape[0], pc.batch, pc.Hq, pc.Hkv, pc.D), 256),
+                                 dtype=torch.uint8, device=dev)
+        self.part_O = [torch.empty(pc.q.shape, dtype=torch.float32 if several else torch.bfloat16, device=dev) for _ in pc.shards]
+        self.part_L = [torch.empty((pc.Tq, pc.Hq), dtype=torch.float32, device=dev) for _ in pc.shards]
+        self.out_O = torch.empty_like(pc.q)
+        self.out_L = torch.empty((pc.Tq, pc.Hq), dtype=torch.float32, device=dev)
+        if dc is not None:
+            self.max_len = int(dc.lens.max())
+            self.ws_dc = torch.empty(esp.esp_decode_workspace_bytes(dc.B, dc.total_tokens, self.max_len, dc.Hq, dc.Hkv, dc.D),
+                                     dtype=torch.uint8, device=dev)
+            self.dO = torch.empty_like(dc.q)
+            self.dL = torch.empty((dc.B, dc.Hq), dtype=torch.float32, device=dev)
+            self.mO = torch.empty_like(dc.q)
+            self.mL = torch.empty_like(self.dL)
+
+    def prefill_shard(self, i, O=None, L=None, ws=None):
+        pc, s, single = self.pc, self.pc.shards[i], self.single
+        self.esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos,
+                                          None if single else pc.cu_q, None if single else s.cu_kv,
+                                          None if single else pc.max_q, None if single else s.max_kv,
+                                          softmax_scale=pc.scale, causal=pc.causal, O=self.part_O[i] if O is None else O,
+                                          LSE=self.part_L[i] if L is None else L, workspace=self.ws_pf if ws is None else ws)
+
+    def __call__(self, rec=None):
+        esp, pc, dc = self.esp, self.pc, self.dc
+        e = [self.torch.cuda.Event(enable_timing=True) for _ in range(6)] if rec is not None else None
+        if e: e[0].record()
+        for i in range(len(pc.shards)):
+            self.prefill_shard(i)
+        if e: e[1].record()
+        if len(pc.shards) > 1:
+            esp.esp_merge_partials(self.part_O, self.part_L, O=self.out_O, LSE=self.out_L)
+        if e: e[2].record()
+        if dc is not None:
+            esp.esp_kv_append(dc.new_k, dc.new_v, dc.new_slots, dc.k_pool, dc.v_pool)
+            if e: e[3].record()
+            esp.esp_partial_attn_decode(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, self.max_len,
+                                        softmax_scale=dc.scale, O=self.dO, LSE=self.dL, workspace=self.ws_dc)
+            if e: e[4].record()
+            esp.esp_merge_partials([self.dO] + list(dc.peer_O), [self.dL] + list(dc.peer_LSE), O=self.mO, LSE=self.mL)
+            if e: e[5].record()
+        if rec is not None:
+            rec.append(e)
+
+
+def time_steps(torch, step, steps, warmup):
+    """`warmup` untimed and `steps` timed passes; returns (event records, wall seconds of the timed passes)."""
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    recs = []
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step(recs)
+    torch.cuda.synchronize()
+    return recs, time.perf_counter() - t0
+
+
+def summarize(recs, pc, dc):
+    """Per-phase averages of the event records, in the units of the metric."""
+    avg = lambda i, j: sum(e[i].elapsed_time(e[j]) for e in recs) / len(recs)   # ms
+
+    def spread(i, j):
+        v = sorted(e[i].elapsed_time(e[j]) for e in recs)
+        return {"min": v[0], "median": v[len(v) // 2], "max": v[-1]}
+
+    n_calls = len(pc.shards)
+    ms_prefill = avg(0, 1)
+    flops = pc.flops()
+    tflops = flops / (ms_prefill * 1e-3) / 1e12
+    out = {"prefill": {"ms_all_shards": ms_prefill, "ms_all_shards_spread": spread(0, 1), "ms_per_shard_call": ms_prefill / n_calls,
+                       "ms_merge": avg(1, 2) if n_calls > 1 else 0.0, "partials": "fp32" if n_calls > 1 else "bf16 (one shard, no merge)",
+                       "tflops": tflops, "pct_of_peak": 100.0 * tflops / PEAK_BF16_TFLOPS, "flops": flops, "launches_per_step": n_calls}}
+    if dc is not None:
+        ms_decode = avg(3, 4)
+        byts = dc.kv_bytes()
+        gbs = byts / (ms_decode * 1e-3) / 1e9
+        out["decode"] = {"ms": ms_decode, "ms_spread": spread(3, 4), "ms_append": avg(2, 3), "ms_merge": avg(4, 5), "bytes": byts, "gbs": gbs,
+                         "pct_of_peak": 100.0 * gbs / PEAK_HBM_GBS, "B": dc.B, "total_tokens": dc.total_tokens, "sigma": 1.0}
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -175,64 +282,14 @@ def main():
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    pc = dc = None
     note("generating the synthetic inputs of workload '%s'" % args.workload)
-    if args.workload == "lwm7b":
-        pc = wl.config2_prefill(dev)
-        lens = wl.lognormal_lengths(64, 8192, 1024, 131072, 2)
-        order = np.argsort(lens)
-        dc = wl.config3_decode(dev, sample_reqs=[int(i) for i in order[::4]])
-        name = "LWM-7B shape: prefill chunk 8192 x 4 striped shards of 8192 (configs[1]) + decode B=64 in a 4M-slot pool (configs[2])"
-    elif args.workload == "long":
-        pc = wl.config4_prefill(dev)
-        name = "long-context prefill share: chunk 32768 against 262144 local KV (configs[3])"
-    else:
-        pc = wl.config5_prefill(dev)
-        lens = wl.lognormal_lengths(256, 16384, 512, 1 << 20, 4)
-        order = np.argsort(lens)
-        dc = wl.config5_decode(dev, sample_reqs=[int(order[0]), int(order[len(order) // 2])])
-        name = "mixed iteration: var-len GQA prefill of 6 requests x 4 striped shards + decode B=256 in a 16M-slot pool (configs[4])"
-
-    single = pc.batch == 1
-    ws_pf = torch.empty(max(esp.esp_prefill_workspace_bytes(pc.Tq, pc.shards[0].k.shape[0], pc.batch, pc.Hq, pc.Hkv, pc.D), 256),
-                        dtype=torch.uint8, device=dev)
-    part_O = [torch.empty_like(pc.q) for _ in pc.shards]
-    part_L = [torch.empty((pc.Tq, pc.Hq), dtype=torch.float32, device=dev) for _ in pc.shards]
-    out_O = torch.empty_like(pc.q)
-    out_L = torch.empty((pc.Tq, pc.Hq), dtype=torch.float32, device=dev)
+    pc, dc, name = make_workload(args.workload, wl, np, dev)
+    step = Step(esp, torch, pc, dc, dev)
+    single = step.single
+    ws_pf, part_O, part_L, out_O, out_L = step.ws_pf, step.part_O, step.part_L, step.out_O, step.out_L
     if dc is not None:
-        max_len = int(dc.lens.max())
-        ws_dc = torch.empty(esp.esp_decode_workspace_bytes(dc.B, dc.total_tokens, max_len, dc.Hq, dc.Hkv, dc.D),
-                            dtype=torch.uint8, device=dev)
-        dO = torch.empty_like(dc.q)
-        dL = torch.empty((dc.B, dc.Hq), dtype=torch.float32, device=dev)
-        mO = torch.empty_like(dc.q)
-        mL = torch.empty_like(dL)
-
+        max_len, ws_dc, dO, dL, mO, mL = step.max_len, step.ws_dc, step.dO, step.dL, step.mO, step.mL
     ev = lambda: torch.cuda.Event(enable_timing=True)
-
-    def step(rec=None):
-        e = [ev() for _ in range(6)] if rec is not None else None
-        if e: e[0].record()
-        for i, s in enumerate(pc.shards):
-            esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos,
-                                         None if single else pc.cu_q, None if single else s.cu_kv,
-                                         None if single else pc.max_q, None if single else s.max_kv,
-                                         softmax_scale=pc.scale, causal=pc.causal, O=part_O[i], LSE=part_L[i], workspace=ws_pf)
-        if e: e[1].record()
-        if len(pc.shards) > 1:
-            esp.esp_merge_partials(part_O, part_L, O=out_O, LSE=out_L)
-        if e: e[2].record()
-        if dc is not None:
-            esp.esp_kv_append(dc.new_k, dc.new_v, dc.new_slots, dc.k_pool, dc.v_pool)
-            if e: e[3].record()
-            esp.esp_partial_attn_decode(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, max_len,
-                                        softmax_scale=dc.scale, O=dO, LSE=dL, workspace=ws_dc)
-            if e: e[4].record()
-            esp.esp_merge_partials([dO] + list(dc.peer_O), [dL] + list(dc.peer_LSE), O=mO, LSE=mL)
-            if e: e[5].record()
-        if rec is not None:
-            rec.append(e)
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -241,28 +298,10 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     note("inputs ready; %d warm-up and %d timed steps" % (args.warmup, args.steps))
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    recs = []
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(recs)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-
-    def avg(i, j):
-        return sum(e[i].elapsed_time(e[j]) for e in recs) / len(recs)   # ms
-
-    def spread(i, j):
-        v = sorted(e[i].elapsed_time(e[j]) for e in recs)
-        return {"min": v[0], "median": v[len(v) // 2], "max": v[-1]}
-
-    ms_prefill = avg(0, 1)
-    ms_merge = avg(1, 2) if len(pc.shards) > 1 else 0.0
-    flops = pc.flops()
-    tflops = flops / (ms_prefill * 1e-3) / 1e12
-    n_calls = len(pc.shards)
+    recs, wall = time_steps(torch, step, args.steps, args.warmup)
+    summ = summarize(recs, pc, dc)
+    tflops, flops, n_calls = summ["prefill"]["tflops"], summ["prefill"]["flops"], len(pc.shards)
+    ms_prefill = summ["prefill"]["ms_all_shards"]
     result = {
         "metric": "prefill partial-attn TFLOP/s + decode partial-attn HBM GB/s (% of peak)",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -270,22 +309,17 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": name, "Hq": pc.Hq, "Hkv": pc.Hkv, "head_dim": pc.D, "prefill_Tq": pc.Tq,
                    "prefill_shards": n_calls, "prefill_flops": flops},
-        "prefill": {"ms_all_shards": ms_prefill, "ms_all_shards_spread": spread(0, 1), "ms_per_shard_call": ms_prefill / n_calls, "ms_merge": ms_merge,
-                    "tflops": tflops, "pct_of_peak": 100.0 * tflops / PEAK_BF16_TFLOPS},
+        "prefill": summ["prefill"],
         "roofline": {"kernel": "prefill_kernel", "bound": "mfma", "achieved": tflops, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS, "traffic": None,
                      "launch_ms": ms_prefill / n_calls, "flops_per_launch": flops / n_calls},
     }
     if dc is not None:
-        ms_append, ms_decode, ms_dmerge = avg(2, 3), avg(3, 4), avg(4, 5)
-        byts = dc.kv_bytes()
-        gbs = byts / (ms_decode * 1e-3) / 1e9
-        result["decode"] = {"ms": ms_decode, "ms_append": ms_append, "ms_merge": ms_dmerge, "bytes": byts, "gbs": gbs,
-                            "pct_of_peak": 100.0 * gbs / PEAK_HBM_GBS, "B": dc.B, "total_tokens": dc.total_tokens,
-                            "sigma": 1.0}
+        result["decode"] = summ["decode"]
+        gbs = summ["decode"]["gbs"]
         result["roofline_decode"] = {"kernel": "decode_partial_kernel", "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS,
-                                     "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "traffic": None, "launch_ms": ms_decode,
-                                     "bytes_per_launch": byts}
+                                     "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "traffic": None, "launch_ms": summ["decode"]["ms"],
+                                     "bytes_per_launch": summ["decode"]["bytes"]}
         result["config"].update({"decode_B": dc.B, "decode_total_tokens": dc.total_tokens, "pool_slots": dc.num_slots})
     if args.fit_model:
         result["model_fit"] = fit_model(esp, wl, torch, np, dev)
@@ -328,8 +362,6 @@ def main():
         result["retain"] = {"ms_prefill_alone": t_plain, "ms_prefill_with_retention": t_ret,
                             "overhead_pct": 100.0 * (t_ret / t_plain - 1.0), "rows_retained": n_rows,
                             "bytes_moved": 2 * 2 * n_rows * pc.Hkv * pc.D * 2, "pool_matches": bool(ok)}
-    if "decode" in result:
-        result["decode"]["ms_spread"] = spread(3, 4)
     if args.one_call and single and len(pc.shards) > 1:
         # the same keys in one call: the shards concatenated and put in order of position (any order of rows is a
         # valid shard; ascending positions are what lets whole tiles be skipped or left unmasked)
@@ -450,7 +482,8 @@ def main():
             esp.esp_kv_append(s.k, s.v, slots[-1], kp, vp)
         ws_pool = torch.empty(max(esp.esp_prefill_pool_workspace_bytes(pc.Tq, max(s.k.shape[0] for s in pc.shards), pc.batch, pc.Hq,
                                                                        pc.Hkv, pc.D), 256), dtype=torch.uint8, device=dev)
-        pool_O = [torch.empty_like(x) for x in part_O]; pool_L = [torch.empty_like(x) for x in part_L]
+        pool_O = [torch.empty_like(pc.q) for _ in part_O]; pool_L = [torch.empty_like(x) for x in part_L]
+        dense_O = [torch.empty_like(pc.q) for _ in part_O]
 
         def prefill_all(from_pool):
             for i, s in enumerate(pc.shards):
@@ -464,7 +497,7 @@ def main():
                     esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos,
                                                  None if single else pc.cu_q, None if single else s.cu_kv,
                                                  None if single else pc.max_q, None if single else s.max_kv,
-                                                 softmax_scale=pc.scale, causal=pc.causal, O=part_O[i], LSE=part_L[i], workspace=ws_pf)
+                                                 softmax_scale=pc.scale, causal=pc.causal, O=dense_O[i], LSE=part_L[i], workspace=ws_pf)
 
         times = {}
         for mode in (False, True, False, True):
@@ -476,7 +509,7 @@ def main():
             e1.record(); torch.cuda.synchronize()
             times.setdefault(mode, []).append(e0.elapsed_time(e1) / args.steps)
         t_dense, t_pool = min(times[False]), min(times[True])
-        same = all(torch.equal(a_, b_) for a_, b_ in zip(part_O, pool_O)) and all(torch.equal(a_, b_) for a_, b_ in zip(part_L, pool_L))
+        same = all(torch.equal(a_, b_) for a_, b_ in zip(dense_O, pool_O)) and all(torch.equal(a_, b_) for a_, b_ in zip(part_L, pool_L))
         moved = 2 * 2 * n_rows * pc.Hkv * pc.D * 2                  # K and V, read from the pool and written to the staging rows
         result["from_pool"] = {"ms_dense": t_dense, "ms_from_pool": t_pool, "overhead_pct": 100.0 * (t_pool / t_dense - 1.0),
                                "rows": n_rows, "gather_bytes": moved, "gather_gbs": moved / ((t_pool - t_dense) * 1e-3) / 1e9,
@@ -488,9 +521,28 @@ def main():
             result["roofline_decode"]["traffic"] = tr.get("decode_partial_kernel")
     if not args.no_cpu_baseline:
         import oracle
-        note("timing the CPU oracle on a bounded sample (10-30 s)")
+        note("timing the CPU oracle on the parity samples of this workload")
         result["cpu_baseline"] = cpu_baseline(pc, dc, wl, oracle)
         note("done")
+    if args.workload == "lwm7b" and not args.no_extra:
+        # the other full-size configurations, one after the other with the pools freed in between: the same
+        # step, fewer repetitions, reported under keys of their own (they are not part of `value`)
+        del step, pc, dc, ws_pf, part_O, part_L, out_O, out_L, ws_dc, dO, dL, mO, mL
+        torch.cuda.empty_cache()
+        for which, reps in (("long", 5), ("mixed", 5)):
+            note("extra workload '%s': %d timed steps" % (which, reps))
+            pc2, dc2, name2 = make_workload(which, wl, np, dev)
+            step2 = Step(esp, torch, pc2, dc2, dev)
+            recs2, _ = time_steps(torch, step2, reps, 1)
+            s2 = summarize(recs2, pc2, dc2)
+            tag = "c4" if which == "long" else "c5"
+            result["prefill_" + tag] = dict(s2["prefill"], workload=name2, steps=reps, frac=s2["prefill"]["tflops"] / PEAK_BF16_TFLOPS,
+                                            bound="mfma", peak=PEAK_BF16_TFLOPS, unit="TFLOP/s")
+            if dc2 is not None:
+                result["decode_" + tag] = dict(s2["decode"], workload=name2, steps=reps, frac=s2["decode"]["gbs"] / PEAK_HBM_GBS,
+                                               bound="hbm", peak=PEAK_HBM_GBS, unit="GB/s")
+            del step2, pc2, dc2, recs2
+            torch.cuda.empty_cache()
     print(json.dumps(result), flush=True)
 
 

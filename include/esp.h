@@ -16,7 +16,9 @@
  * Conventions common to all calls
  *   - Every data pointer is DEVICE memory owned by the caller unless a
  *     parameter says "host".  The library never allocates, frees or keeps
- *     device memory and holds no state between calls.
+ *     device memory.  Its only state between calls is process-wide and small:
+ *     a launch counter that tags the prefill workspace (see there) and the two
+ *     debugging switches at the end of this file.
  *   - bf16 tensors are passed as `const void*` (16-bit patterns); layouts are
  *     token-major and dense: Q/O [T, Hq, D], K/V [T, Hkv, D], pools
  *     [S, Hkv, D] (one for K, one for V), LSE [T, Hq] float.
@@ -77,8 +79,14 @@ typedef int32_t esp_status;
  *     only to size the launch).
  *   O [Tq,Hq,D] bf16, LSE [Tq,Hq] float: written for every row.
  *   workspace: at least esp_prefill_workspace_bytes(...) bytes, 256-byte
- *     aligned; contents need not be preserved or initialised.  Calls that
- *     may run at the same time need a workspace each.
+ *     aligned; contents need not be preserved between calls.  It holds work
+ *     counters that are never cleared: every launch tags them with a number of
+ *     its own (a per-process random 32-bit start, then +1 per call), so memory
+ *     that has never been written is mistaken for the current launch's counters
+ *     with probability 2^-32 per fresh workspace (query tiles would then be
+ *     skipped).  A caller that wants certainty zeroes a new workspace once:
+ *     the tag is never 0.  Calls that may run at the same time need a
+ *     workspace each.
  * Positions may be in any order; ascending order inside a request lets whole
  * tiles be skipped or left unmasked.
  */
@@ -93,6 +101,23 @@ esp_status esp_partial_attn_prefill(
 
 size_t esp_prefill_workspace_bytes(int32_t Tq, int32_t Tkv, int32_t batch,
                                    int32_t Hq, int32_t Hkv, int32_t D);
+
+/*
+ * The same call with O [Tq,Hq,D] written as float: for partials that stay on this
+ * GPU until they are combined (the rounds of sequence-parallel prefill, Sec. 2.3:
+ * one call per key-value segment that passes by, one combination at the end), so
+ * that the combined result is rounded to bf16 once, by esp_merge_partials_f32,
+ * and not once per partial and again after the combination.  Everything else,
+ * the workspace included, as in esp_partial_attn_prefill.
+ */
+esp_status esp_partial_attn_prefill_f32(
+    const void* q, const void* k, const void* v,
+    const int32_t* q_pos, const int32_t* kv_pos,
+    const int32_t* cu_q, const int32_t* cu_kv, int32_t batch,
+    int32_t Tq, int32_t Tkv, int32_t max_q, int32_t max_kv,
+    int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale, int32_t causal,
+    float* O, float* LSE,
+    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Decode partial attention (Sec. 4.2, Fig. 8: every instance of the group runs
@@ -133,6 +158,16 @@ size_t esp_decode_workspace_bytes(int32_t B, int32_t total_tokens, int32_t max_l
  */
 esp_status esp_merge_partials(
     const void* const* O_parts, const float* const* LSE_parts, int32_t P,
+    int32_t T, int32_t Hq, int32_t D,
+    void* O, float* LSE_out, void* stream);
+
+/*
+ * The same combination of float partials (O_parts[p]: float [T,Hq,D], as
+ * esp_partial_attn_prefill_f32 writes them); O is still bf16 and must not alias
+ * a partial.
+ */
+esp_status esp_merge_partials_f32(
+    const float* const* O_parts, const float* const* LSE_parts, int32_t P,
     int32_t T, int32_t Hq, int32_t D,
     void* O, float* LSE_out, void* stream);
 
@@ -231,6 +266,19 @@ esp_status esp_plan_prefill_batches(
 esp_status esp_fit_prefill_model(
     const double* sum_len, const double* sum_len_sq, const double* seconds, const double* weights, int32_t n,
     double* coef);
+
+/*
+ * Debugging switches (process-wide; each returns the previous setting).
+ *   esp_debug_set_validate: the host-side check of device index arrays described at
+ *     the top (default: ESP_DEBUG_VALIDATE in the environment, read once at load time).
+ *   esp_debug_set_prefill_sync_ticks: the longest time, in ticks of the 100 MHz wall
+ *     clock, that prefill workgroups sharing a key-value head wait for each other at
+ *     the start of a round (default 15000, or ESP_PREFILL_SYNC_TICKS read once at load
+ *     time; 0 makes every such wait give up at once; negative restores the default).
+ *     It changes timing only, never results.
+ */
+int32_t esp_debug_set_validate(int32_t on);
+int32_t esp_debug_set_prefill_sync_ticks(int32_t ticks);
 
 /* Message of the last error on the calling thread (static storage, never NULL). */
 const char* esp_last_error(void);

@@ -24,6 +24,8 @@ EXPORTS = (
     "esp_plan_prefill_batches", "esp_fit_prefill_model",
     "esp_kv_gather", "esp_partial_attn_prefill_pool", "esp_prefill_pool_workspace_bytes",
     "esp_probe_mfma_bf16", "esp_probe_stream_read",
+    "esp_partial_attn_prefill_f32", "esp_merge_partials_f32",
+    "esp_debug_set_validate", "esp_debug_set_prefill_sync_ticks",
 )
 
 
@@ -42,6 +44,14 @@ def _load() -> ctypes.CDLL:
     vp, i32, i64, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
     L.esp_partial_attn_prefill.argtypes = [vp] * 7 + [i32] * 8 + [f32, i32, vp, vp, vp, sz, vp]
     L.esp_partial_attn_prefill.restype = i32
+    L.esp_partial_attn_prefill_f32.argtypes = L.esp_partial_attn_prefill.argtypes
+    L.esp_partial_attn_prefill_f32.restype = i32
+    L.esp_merge_partials_f32.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp]
+    L.esp_merge_partials_f32.restype = i32
+    L.esp_debug_set_validate.argtypes = [i32]
+    L.esp_debug_set_validate.restype = i32
+    L.esp_debug_set_prefill_sync_ticks.argtypes = [i32]
+    L.esp_debug_set_prefill_sync_ticks.restype = i32
     L.esp_prefill_workspace_bytes.argtypes = [i32] * 6
     L.esp_prefill_workspace_bytes.restype = sz
     L.esp_partial_attn_decode.argtypes = [vp, vp, vp, i64, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, vp, vp, sz, vp]
@@ -111,6 +121,16 @@ def _workspace(nbytes: int, device) -> torch.Tensor:
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
 
 
+def esp_debug_set_validate(on: bool) -> bool:
+    """Host-side check of device index arrays before every launch (a debugging aid); returns the previous setting."""
+    return bool(lib.esp_debug_set_validate(1 if on else 0))
+
+
+def esp_debug_set_prefill_sync_ticks(ticks: int) -> int:
+    """Longest start-of-round wait of the prefill kernel in 10 ns ticks (negative: the default); returns the previous value."""
+    return int(lib.esp_debug_set_prefill_sync_ticks(int(ticks)))
+
+
 def esp_prefill_workspace_bytes(Tq, Tkv, batch, Hq, Hkv, D) -> int:
     return int(lib.esp_prefill_workspace_bytes(Tq, Tkv, batch, Hq, Hkv, D))
 
@@ -120,9 +140,11 @@ def esp_decode_workspace_bytes(B, total_tokens, max_len, Hq, Hkv, D) -> int:
 
 
 def esp_partial_attn_prefill(q, k, v, q_pos, kv_pos, cu_q=None, cu_kv=None, max_q=None, max_kv=None,
-                             softmax_scale=None, causal=True, O=None, LSE=None, workspace=None):
+                             softmax_scale=None, causal=True, O=None, LSE=None, workspace=None, out_dtype=torch.bfloat16):
     """q [Tq,Hq,D], k/v [Tkv,Hkv,D] bf16; q_pos/kv_pos int32; cu_q/cu_kv int32 [batch+1] or None.
-    Returns (O bf16 [Tq,Hq,D], LSE fp32 [Tq,Hq]) of attention against this one KV shard."""
+    Returns (O [Tq,Hq,D], LSE fp32 [Tq,Hq]) of attention against this one KV shard.  O is bf16
+    (esp_partial_attn_prefill) or, if `O` is a float32 tensor or out_dtype is torch.float32, fp32
+    (esp_partial_attn_prefill_f32)."""
     _dev(q, torch.bfloat16, "q"); _dev(k, torch.bfloat16, "k"); _dev(v, torch.bfloat16, "v")
     _dev(q_pos, torch.int32, "q_pos"); _dev(kv_pos, torch.int32, "kv_pos")
     Tq, Hq, D = q.shape
@@ -142,15 +164,18 @@ def esp_partial_attn_prefill(q, k, v, q_pos, kv_pos, cu_q=None, cu_kv=None, max_
     if softmax_scale is None:
         softmax_scale = D ** -0.5
     if O is None:
-        O = torch.empty_like(q)
+        O = torch.empty(q.shape, dtype=out_dtype, device=q.device)
     if LSE is None:
         LSE = torch.empty((Tq, Hq), dtype=torch.float32, device=q.device)
-    _dev(O, torch.bfloat16, "O"); _dev(LSE, torch.float32, "LSE")
+    if O.dtype not in (torch.bfloat16, torch.float32):
+        raise ValueError("prefill: O must be bf16 or fp32")
+    _dev(O, O.dtype, "O"); _dev(LSE, torch.float32, "LSE")
     if O.shape != q.shape or LSE.shape != (Tq, Hq):
         raise ValueError("prefill: output shape mismatch")
     if workspace is None:
         workspace = _workspace(esp_prefill_workspace_bytes(Tq, Tkv, batch, Hq, Hkv, D), q.device)
-    _check(lib.esp_partial_attn_prefill(_ptr(q), _ptr(k), _ptr(v), _ptr(q_pos), _ptr(kv_pos), _ptr(cu_q), _ptr(cu_kv),
+    call = lib.esp_partial_attn_prefill_f32 if O.dtype == torch.float32 else lib.esp_partial_attn_prefill
+    _check(call(_ptr(q), _ptr(k), _ptr(v), _ptr(q_pos), _ptr(kv_pos), _ptr(cu_q), _ptr(cu_kv),
                                         batch, Tq, Tkv, int(max_q), int(max_kv), Hq, Hkv, D, float(softmax_scale),
                                         int(bool(causal)), _ptr(O), _ptr(LSE), _ptr(workspace), workspace.numel(),
                                         _stream()))
@@ -185,14 +210,18 @@ def esp_partial_attn_decode(q, k_pool, v_pool, slot_idx, seq_offsets, max_len, s
 
 def esp_merge_partials(O_parts: Sequence[torch.Tensor], LSE_parts: Sequence[torch.Tensor], O=None, LSE=None,
                        want_lse: bool = True):
-    """Combine P partial results (bf16 [T,Hq,D], fp32 [T,Hq]) into (O bf16, LSE fp32 or None)."""
+    """Combine P partial results (O_p bf16 or, all of them, fp32 [T,Hq,D]; LSE_p fp32 [T,Hq]) into
+    (O bf16, LSE fp32 or None): esp_merge_partials or esp_merge_partials_f32 by the partials' type."""
     P = len(O_parts)
     if P != len(LSE_parts):
         raise ValueError("merge: O_parts and LSE_parts differ in length")
     if P == 0:
         raise ValueError("merge: need at least one partial")
+    pdt = O_parts[0].dtype
+    if pdt not in (torch.bfloat16, torch.float32):
+        raise ValueError("merge: partials must be bf16 or fp32")
     for i in range(P):
-        _dev(O_parts[i], torch.bfloat16, f"O_parts[{i}]"); _dev(LSE_parts[i], torch.float32, f"LSE_parts[{i}]")
+        _dev(O_parts[i], pdt, f"O_parts[{i}]"); _dev(LSE_parts[i], torch.float32, f"LSE_parts[{i}]")
         if O_parts[i].shape != O_parts[0].shape or LSE_parts[i].shape != O_parts[0].shape[:-1]:
             raise ValueError("merge: partial shapes differ")
     *lead, Hq, D = O_parts[0].shape
@@ -200,12 +229,14 @@ def esp_merge_partials(O_parts: Sequence[torch.Tensor], LSE_parts: Sequence[torc
     for s in lead:
         T *= s
     if O is None:
-        O = torch.empty_like(O_parts[0])
+        O = torch.empty(O_parts[0].shape, dtype=torch.bfloat16, device=O_parts[0].device)
+    _dev(O, torch.bfloat16, "O")
     if LSE is None and want_lse:
         LSE = torch.empty(O_parts[0].shape[:-1], dtype=torch.float32, device=O.device)
     op = (ctypes.c_void_p * P)(*[t.data_ptr() for t in O_parts])
     lp = (ctypes.c_void_p * P)(*[t.data_ptr() for t in LSE_parts])
-    _check(lib.esp_merge_partials(op, lp, P, T, Hq, D, _ptr(O), _ptr(LSE), _stream()))
+    call = lib.esp_merge_partials_f32 if pdt == torch.float32 else lib.esp_merge_partials
+    _check(call(op, lp, P, T, Hq, D, _ptr(O), _ptr(LSE), _stream()))
     return O, LSE
 
 

@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
 #include <vector>
 
 #include "esp_common.h"
@@ -32,10 +33,11 @@ static bool heads_ok(int32_t Hq, int32_t Hkv) { return Hq > 0 && Hkv > 0 && Hq %
 
 // ESP_DEBUG_VALIDATE=1 in the environment: the content of the device index arrays, trusted otherwise, is checked on
 // the host before the launch.  A debugging aid: it waits for the stream and copies the arrays back.
-static bool debug_validate() {
+static std::atomic<int> g_validate{[] {             // the environment is read once, when the library is loaded
     const char* e = getenv("ESP_DEBUG_VALIDATE");
-    return e && strcmp(e, "0") != 0 && e[0] != 0;
-}
+    return (e && strcmp(e, "0") != 0 && e[0] != 0) ? 1 : 0;
+}()};
+static bool debug_validate() { return g_validate.load(std::memory_order_relaxed) != 0; }
 static bool fetch_i32(const int32_t* dev, size_t n, hipStream_t stream, std::vector<int32_t>& out) {
     out.resize(n);
     if (n == 0) return true;
@@ -77,6 +79,9 @@ using namespace esp;
 extern "C" {
 
 const char* esp_last_error(void) { return g_err; }
+
+int32_t esp_debug_set_validate(int32_t on) { return g_validate.exchange(on ? 1 : 0, std::memory_order_relaxed); }
+int32_t esp_debug_set_prefill_sync_ticks(int32_t ticks) { return set_prefill_sync_ticks(ticks); }
 const char* esp_version(void) { return "esp 0.1 gfx950"; }
 
 size_t esp_prefill_workspace_bytes(int32_t Tq, int32_t Tkv, int32_t batch, int32_t Hq, int32_t Hkv, int32_t D) {
@@ -91,11 +96,11 @@ size_t esp_decode_workspace_bytes(int32_t B, int32_t total_tokens, int32_t max_l
     return decode_workspace_bytes(B, total_tokens, Hq, Hkv);
 }
 
-esp_status esp_partial_attn_prefill(const void* q, const void* k, const void* v, const int32_t* q_pos,
-                                    const int32_t* kv_pos, const int32_t* cu_q, const int32_t* cu_kv, int32_t batch,
-                                    int32_t Tq, int32_t Tkv, int32_t max_q, int32_t max_kv, int32_t Hq, int32_t Hkv,
-                                    int32_t D, float softmax_scale, int32_t causal, void* O, float* LSE,
-                                    void* workspace, size_t workspace_bytes, void* stream) {
+static esp_status prefill_entry(const void* q, const void* k, const void* v, const int32_t* q_pos,
+                                const int32_t* kv_pos, const int32_t* cu_q, const int32_t* cu_kv, int32_t batch,
+                                int32_t Tq, int32_t Tkv, int32_t max_q, int32_t max_kv, int32_t Hq, int32_t Hkv,
+                                int32_t D, float softmax_scale, int32_t causal, int32_t o_f32, void* O, float* LSE,
+                                void* workspace, size_t workspace_bytes, void* stream) {
     if (Tq < 0 || Tkv < 0 || batch < 1 || max_q < 0 || max_kv < 0)
         return fail(ESP_ERR_INVALID_ARG, "prefill: negative size or batch < 1");
     if (!heads_ok(Hq, Hkv)) return fail(ESP_ERR_INVALID_ARG, "prefill: Hq=%d must be a positive multiple of Hkv=%d", Hq, Hkv);
@@ -119,7 +124,25 @@ esp_status esp_partial_attn_prefill(const void* q, const void* k, const void* v,
         if (st != ESP_OK) return st;
     }
     return launch_prefill(q, k, v, q_pos, kv_pos, cu_q, cu_kv, batch, Tq, Tkv, max_q, max_kv, Hq, Hkv,
-                          softmax_scale, causal, O, LSE, workspace, workspace_bytes, (hipStream_t)stream);
+                          softmax_scale, causal, o_f32, O, LSE, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+esp_status esp_partial_attn_prefill(const void* q, const void* k, const void* v, const int32_t* q_pos,
+                                    const int32_t* kv_pos, const int32_t* cu_q, const int32_t* cu_kv, int32_t batch,
+                                    int32_t Tq, int32_t Tkv, int32_t max_q, int32_t max_kv, int32_t Hq, int32_t Hkv,
+                                    int32_t D, float softmax_scale, int32_t causal, void* O, float* LSE,
+                                    void* workspace, size_t workspace_bytes, void* stream) {
+    return prefill_entry(q, k, v, q_pos, kv_pos, cu_q, cu_kv, batch, Tq, Tkv, max_q, max_kv, Hq, Hkv, D, softmax_scale, causal, 0,
+                         O, LSE, workspace, workspace_bytes, stream);
+}
+
+esp_status esp_partial_attn_prefill_f32(const void* q, const void* k, const void* v, const int32_t* q_pos,
+                                        const int32_t* kv_pos, const int32_t* cu_q, const int32_t* cu_kv, int32_t batch,
+                                        int32_t Tq, int32_t Tkv, int32_t max_q, int32_t max_kv, int32_t Hq, int32_t Hkv,
+                                        int32_t D, float softmax_scale, int32_t causal, float* O, float* LSE,
+                                        void* workspace, size_t workspace_bytes, void* stream) {
+    return prefill_entry(q, k, v, q_pos, kv_pos, cu_q, cu_kv, batch, Tq, Tkv, max_q, max_kv, Hq, Hkv, D, softmax_scale, causal, 1,
+                         O, LSE, workspace, workspace_bytes, stream);
 }
 
 esp_status esp_probe_mfma_bf16(const void* operands, int64_t operand_bytes, int32_t iters, void* sink, int64_t* flops,
@@ -209,8 +232,8 @@ esp_status esp_partial_attn_decode(const void* q, const void* k_pool, const void
                          workspace, workspace_bytes, (hipStream_t)stream);
 }
 
-esp_status esp_merge_partials(const void* const* O_parts, const float* const* LSE_parts, int32_t P, int32_t T,
-                              int32_t Hq, int32_t D, void* O, float* LSE_out, void* stream) {
+static esp_status merge_entry(const void* const* O_parts, const float* const* LSE_parts, int32_t P, int32_t T,
+                              int32_t Hq, int32_t D, int32_t parts_f32, void* O, float* LSE_out, void* stream) {
     if (P < 1 || P > ESP_MAX_PARTIALS) return fail(ESP_ERR_INVALID_ARG, "merge: P=%d outside 1..%d", P, ESP_MAX_PARTIALS);
     if (T < 0 || Hq <= 0) return fail(ESP_ERR_INVALID_ARG, "merge: negative size");
     if (D != kHeadDim) return fail(ESP_ERR_UNSUPPORTED, "merge: head_dim %d unsupported (only 128)", D);
@@ -224,7 +247,19 @@ esp_status esp_merge_partials(const void* const* O_parts, const float* const* LS
         a.LSE_parts[p] = LSE_parts[p];
     }
     for (int p = P; p < ESP_MAX_PARTIALS; ++p) { a.O_parts[p] = nullptr; a.LSE_parts[p] = nullptr; }
-    return launch_merge(a, P, (int64_t)T * Hq, O, LSE_out, (hipStream_t)stream);
+    return launch_merge(a, P, (int64_t)T * Hq, parts_f32, O, LSE_out, (hipStream_t)stream);
+}
+
+esp_status esp_merge_partials(const void* const* O_parts, const float* const* LSE_parts, int32_t P, int32_t T,
+                              int32_t Hq, int32_t D, void* O, float* LSE_out, void* stream) {
+    return merge_entry(O_parts, LSE_parts, P, T, Hq, D, 0, O, LSE_out, stream);
+}
+
+esp_status esp_merge_partials_f32(const float* const* O_parts, const float* const* LSE_parts, int32_t P, int32_t T,
+                                  int32_t Hq, int32_t D, void* O, float* LSE_out, void* stream) {
+    for (int p = 0; O_parts && p < P && p < ESP_MAX_PARTIALS; ++p)
+        if (O_parts[p] == O && O) return fail(ESP_ERR_INVALID_ARG, "merge: the bf16 output must not alias an fp32 partial");
+    return merge_entry((const void* const*)O_parts, LSE_parts, P, T, Hq, D, 1, O, LSE_out, stream);
 }
 
 esp_status esp_kv_append(const void* k, const void* v, const int32_t* slot_idx, int32_t T, void* k_pool, void* v_pool,

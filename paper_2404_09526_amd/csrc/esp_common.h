@@ -47,7 +47,7 @@ esp_status launch_kv_gather(const void* k_pool, const void* v_pool, const int32_
 esp_status launch_probe_mfma(const void* operands, int64_t operand_bytes, int32_t iters, void* sink, int64_t* flops,
                              hipStream_t stream);
 esp_status launch_probe_read(const void* src, int64_t bytes, void* sink, hipStream_t stream);
-esp_status launch_merge(const MergeArgs& parts, int32_t P, int64_t pairs, void* O, float* LSE_out,
+esp_status launch_merge(const MergeArgs& parts, int32_t P, int64_t pairs, int32_t parts_f32, void* O, float* LSE_out,
                         hipStream_t stream);
 
 size_t decode_workspace_bytes(int32_t B, int32_t total_tokens, int32_t Hq, int32_t Hkv);
@@ -56,11 +56,12 @@ esp_status launch_decode(const void* q, const void* k_pool, const void* v_pool, 
                          float softmax_scale, void* O, float* LSE, void* workspace, size_t workspace_bytes,
                          hipStream_t stream);
 
+int32_t set_prefill_sync_ticks(int32_t ticks);   // returns the previous value; negative restores the built-in default
 size_t prefill_workspace_bytes(int32_t Tq, int32_t Tkv, int32_t batch, int32_t Hq, int32_t Hkv);
 esp_status launch_prefill(const void* q, const void* k, const void* v, const int32_t* q_pos, const int32_t* kv_pos,
                           const int32_t* cu_q, const int32_t* cu_kv, int32_t batch, int32_t Tq, int32_t Tkv,
                           int32_t max_q, int32_t max_kv, int32_t Hq, int32_t Hkv, float softmax_scale,
-                          int32_t causal, void* O, float* LSE, void* workspace, size_t workspace_bytes,
+                          int32_t causal, int32_t o_f32, void* O, float* LSE, void* workspace, size_t workspace_bytes,
                           hipStream_t stream);
 
 }  // namespace esp

@@ -70,6 +70,19 @@ static uint32_t next_launch_tag() {
     const uint32_t t = tag.fetch_add(1, std::memory_order_relaxed) + 1;
     return t ? t : tag.fetch_add(1, std::memory_order_relaxed) + 1;   // never 0: cleared counters carry tag 0
 }
+// Longest start-of-round wait.  The default comes from ESP_PREFILL_SYNC_TICKS in the environment, read once when the
+// library is loaded; esp_debug_set_prefill_sync_ticks replaces it (0: every wait gives up at once, the path a
+// missing workgroup would cause).
+static std::atomic<int32_t> g_sync_ticks{[] {
+    if (const char* e = getenv("ESP_PREFILL_SYNC_TICKS")) {
+        const long v = strtol(e, nullptr, 10);
+        if (v >= 0 && v <= 1000000) return (int32_t)v;
+    }
+    return (int32_t)kSyncTicks;
+}()};
+int32_t set_prefill_sync_ticks(int32_t ticks) {
+    return g_sync_ticks.exchange(ticks < 0 ? (int32_t)kSyncTicks : ticks > 1000000 ? 1000000 : ticks, std::memory_order_relaxed);
+}
 size_t prefill_workspace_bytes(int32_t Tq, int32_t Tkv, int32_t batch, int32_t Hq, int32_t Hkv) {
     (void)Tq; (void)Tkv; (void)batch; (void)Hkv;
     return ((size_t)8 * (2 + (size_t)(Hq > 0 ? Hq : 0)) + 255) / 256 * 256;   // pool and exit counters + one count per query head
@@ -78,8 +91,8 @@ size_t prefill_workspace_bytes(int32_t Tq, int32_t Tkv, int32_t batch, int32_t H
 struct PrefillArgs {
     const uint16_t* q; const uint16_t* k; const uint16_t* v;
     const int32_t* q_pos; const int32_t* kv_pos; const int32_t* cu_q; const int32_t* cu_kv;
-    uint16_t* O; float* LSE;
-    int32_t batch, Tq, Tkv, Hq, Hkv, causal;
+    void* O; float* LSE;              // O: bf16 [Tq, Hq, 128], or fp32 of the same shape when o_f32 is set
+    int32_t batch, Tq, Tkv, Hq, Hkv, causal, o_f32;
     int32_t q_tiles, heads_per_xcd;   // upper bound of the number of query tiles; query heads per XCD (0: no split)
     unsigned long long* pool;         // counter of the item pool: launch tag (high word), draws so far (low word)
     uint32_t tag;                     // this launch's tag
@@ -394,8 +407,9 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     // of it rescales by an exact power of two) and only when it has to: lim is the largest tile sum
     // accepted without a move, -1 while the row has not seen a key yet (m_use is then a stand-in 0).
     float m_use = 0.f, lim = -1.f;
-    float lsum = 0.f;          // running sum of exp2 over this lane's half of the keys
-    float psum = 0.f, p0 = 0.f, p1 = 0.f;
+    float lsum = 0.f;          // running sum of exp2 over this lane's half of the keys (for the log-sum-exp)
+    float lsum_r = 0.f;        // the same sum over the probabilities as rounded to bf16 (what O^T accumulates)
+    float psum = 0.f, psum_r = 0.f, p0 = 0.f, p1 = 0.f;
 
     floatx16 sbuf[2][2];       // S^T of two tiles in flight: [tile parity][kvb]
     union PFrag { uint32_t u[4]; bf16x8 v; };
@@ -443,7 +457,9 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
 
     // probabilities of score pair c (0..15) of the current tile, in two parts placed behind the two MFMAs of a
     // step: exp2 first, then the fp32 partial sum (of the unrounded values: the log-sum-exp has to be good to
-    // 1e-4) and the bf16 pack
+    // 1e-4), the bf16 pack, and the sum of the packed values (one dot product with (1, 1)).  O is normalised by
+    // the latter: then it is a convex combination of value rows whatever the rounding of the weights did, a
+    // rounding error common to the weights cancels, and a row that sees a single key returns that row exactly.
     auto pair_exp = [&](const floatx16 (&sc)[2], int c) {
         const int kvb = c >> 3, r = 2 * (c & 7);
         p0 = __builtin_amdgcn_exp2f(fmaf(sc[kvb][r], a.scale_log2, -m_use));
@@ -453,7 +469,9 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         if (c == 0) psum = p0 + p1;
         else { psum += p0; psum += p1; }
         const uint32_t pk = pack_bf16(p0, p1);
-        asm volatile("" :: "v"(pk), "v"(psum));   // sum and pack here, not in a bunch further down
+        psum_r = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), __builtin_bit_cast(bf16x2, 0x3f803f80u),
+                                                 c == 0 ? 0.f : psum_r, false);
+        asm volatile("" :: "v"(pk), "v"(psum), "v"(psum_r));   // sums and pack here, not in a bunch further down
         pf[c >> 3][(c >> 2) & 1].u[c & 3] = pk;
     };
 
@@ -468,16 +486,23 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     int32_t* lds_unsafe = (int32_t*)(smem + kLdsFlag);
     auto close_tile = [&](const floatx16 (&sc)[2]) {
         lsum += psum;
+        lsum_r += psum_r;
         if (__builtin_amdgcn_ballot_w64(!(psum <= lim)) != 0) {
             const float tm = row_max(sc);
-            const bool move = !(psum <= lim) && tm != -INFINITY;     // a fresh row whose tile is all masked stays fresh
-            const bool bad = move && (!(psum <= 0x1p100f) || (lim < 0.f && !(fabsf(tm) <= 64.f)));
+            // A query row is held by two lanes (l and l | 32), each with the sum over its half of the tile's keys:
+            // the decision must be the row's, or one half would go on with the old offset while the other one
+            // moves.  Coded as a number so that a NaN sum counts too: 1 = above the limit, 3 = also out of range.
+            const float mine = !(psum <= 0x1p100f) ? 3.f : !(psum <= lim) ? 1.f : 0.f;
+            const float rows = half_swap_max(mine);
+            const bool move = rows >= 1.f && tm != -INFINITY;        // a fresh row whose tile is all masked stays fresh
+            const bool bad = move && (rows >= 3.f || (lim < 0.f && !(fabsf(tm) <= 64.f)));
             if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0) *lds_unsafe = 1;
             const float m_new = move ? m_use + ceilf(tm - m_use) : m_use;     // whole steps: alpha is a power of two
             const float alpha = __builtin_amdgcn_exp2f(m_use - m_new);        // 1 where nothing moves
             m_use = m_new;
             if (move) lim = kSumLimit;
             lsum *= alpha;
+            lsum_r *= alpha;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -659,6 +684,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     if (__builtin_amdgcn_readfirstlane(*lds_unsafe) != 0) {
         float m_ref = -INFINITY;
         lsum = 0.f;
+        lsum_r = 0.f;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -686,6 +712,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
             const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_ref - m_new);
             m_ref = m_new;
             lsum *= alpha;
+            lsum_r *= alpha;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -694,6 +721,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
             for (int c = 0; c < 16; ++c) { pair_exp(sc, c); pair_sum_pack(c); }
             lsum += psum;
+            lsum_r += psum_r;
 #pragma unroll
             for (int p = 0; p < 16; ++p) {
                 read_v(0, 0, p);
@@ -706,11 +734,13 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
 
     // ---- epilogue: normalise, write O (bf16) and LSE (natural log)
     const float ltot = half_swap_sum(lsum);
-    const float inv = ltot > 0.f ? 1.0f / ltot : 0.f;
+    const float ltot_r = half_swap_sum(lsum_r);
+    const float inv = ltot_r > 0.f ? 1.0f / ltot_r : 0.f;
     // O goes through LDS so that it leaves in whole rows: a lane holds 8-byte pieces of one row, 16 of them spread
     // over the 256 bytes; written to a wavefront-private 32 x 272-byte block (the K stages are free by now: the
     // barrier above ended all tile reads) they come back as 16 lanes x 16 bytes per row, four rows per store.
-    {
+    const int rows_here = min(32, q_hi - (q_lo + wave * 32));       // rows of this wavefront that exist (may be <= 0)
+    if (!a.o_f32) {
         unsigned char* blk = smem + kLdsK + wave * (32 * kKRow);
 #pragma unroll
         for (int db = 0; db < 4; ++db)
@@ -722,9 +752,8 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
                 *(uint2*)(blk + qi * kKRow + (32 * db + 8 * bb + 4 * hi) * 2) = w;
             }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");          // same wavefront wrote what it reads next
-        const int rows_here = min(32, q_hi - (q_lo + wave * 32));   // rows of this wavefront that exist (may be <= 0)
         const int rsub = lane >> 4, c16 = lane & 15;
-        uint16_t* orow = a.O + ((int64_t)(q_lo + wave * 32 + rsub) * a.Hq + h) * kHeadDim + 8 * c16;
+        uint16_t* orow = (uint16_t*)a.O + ((int64_t)(q_lo + wave * 32 + rsub) * a.Hq + h) * kHeadDim + 8 * c16;
         const int64_t ostep = (int64_t)4 * a.Hq * kHeadDim;
         if (rows_here >= 32) {                                      // all rows exist: eight stores in a row, no branches
             uint4 w[8];
@@ -738,6 +767,36 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
                 const int r = 4 * i + rsub;
                 const uint4 w = *(const uint4*)(blk + r * kKRow + 16 * c16);
                 if (r < rows_here) *(uint4*)(orow + i * ostep) = w;
+            }
+        }
+    } else {
+        // fp32 output (a partial that stays on this GPU until the merge): rows of 512 bytes, padded to 528 in LDS;
+        // the eight blocks of 32 rows fill the V and K stages exactly.  Two rows per store, 16 stores.
+        constexpr int kFRow = 4 * kHeadDim + 16;
+        static_assert(kPfWaves * 32 * kFRow <= kStages * (kTileBytes + kKTileBytes), "fp32 output staging must fit the tile stages");
+        unsigned char* blk = smem + kLdsV + wave * (32 * kFRow);
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int bb = 0; bb < 4; ++bb)
+                *(float4*)(blk + qi * kFRow + (32 * db + 8 * bb + 4 * hi) * 4) =
+                    make_float4(oacc[db][4 * bb + 0] * inv, oacc[db][4 * bb + 1] * inv, oacc[db][4 * bb + 2] * inv, oacc[db][4 * bb + 3] * inv);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        const int rsub = lane >> 5, c32 = lane & 31;
+        float* orow = (float*)a.O + ((int64_t)(q_lo + wave * 32 + rsub) * a.Hq + h) * kHeadDim + 4 * c32;
+        const int64_t ostep = (int64_t)2 * a.Hq * kHeadDim;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            uint4 w[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) w[i] = *(const uint4*)(blk + (2 * (8 * half + i) + rsub) * kFRow + 16 * c32);
+            if (rows_here >= 32) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) *(uint4*)(orow + (8 * half + i) * ostep) = w[i];
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (2 * (8 * half + i) + rsub < rows_here) *(uint4*)(orow + (8 * half + i) * ostep) = w[i];
             }
         }
     }
@@ -832,13 +891,13 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
 esp_status launch_prefill(const void* q, const void* k, const void* v, const int32_t* q_pos, const int32_t* kv_pos,
                           const int32_t* cu_q, const int32_t* cu_kv, int32_t batch, int32_t Tq, int32_t Tkv,
                           int32_t max_q, int32_t max_kv, int32_t Hq, int32_t Hkv, float softmax_scale,
-                          int32_t causal, void* O, float* LSE, void* workspace, size_t workspace_bytes,
+                          int32_t causal, int32_t o_f32, void* O, float* LSE, void* workspace, size_t workspace_bytes,
                           hipStream_t stream) {
     (void)max_q; (void)max_kv;
     PrefillArgs a;
     a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
     a.q_pos = q_pos; a.kv_pos = kv_pos; a.cu_q = cu_q; a.cu_kv = cu_kv;
-    a.O = (uint16_t*)O; a.LSE = LSE;
+    a.O = O; a.LSE = LSE; a.o_f32 = o_f32 ? 1 : 0;
     a.batch = batch; a.Tq = Tq; a.Tkv = Tkv; a.Hq = Hq; a.Hkv = Hkv; a.causal = causal ? 1 : 0;
     a.scale_log2 = softmax_scale * kLog2e;
     a.q_tiles = prefill_q_tiles_bound(Tq, batch);
@@ -858,13 +917,7 @@ esp_status launch_prefill(const void* q, const void* k, const void* v, const int
     a.group_sync = (a.heads_per_xcd > 0 && batch == 1 && Tkv >= 512 * kBN && (int64_t)Tkv >= 8 * (int64_t)Tq &&
                     (cus / 8) % a.heads_per_xcd == 0 &&
                     8 * (2 + 8 * (size_t)a.heads_per_xcd) <= workspace_bytes) ? 1 : 0;
-    // ESP_PREFILL_SYNC_TICKS in the environment replaces the longest wait (0: every wait gives up at once; a test uses
-    // it to run the path a missing workgroup would take)
-    a.sync_ticks = (int32_t)kSyncTicks;
-    if (const char* e = getenv("ESP_PREFILL_SYNC_TICKS")) {
-        const long v = strtol(e, nullptr, 10);
-        if (v >= 0 && v <= 1000000) a.sync_ticks = (int32_t)v;
-    }
+    a.sync_ticks = g_sync_ticks.load(std::memory_order_relaxed);
     hipLaunchKernelGGL(prefill_kernel, dim3(grid), dim3(kPfWaves * 64), 0, stream, a);
     return check_launch("prefill_kernel");
 }

@@ -233,6 +233,47 @@ def decode_pool(name: str, lens: Sequence[int], num_slots: int, Hq: int, Hkv: in
                       new_k, new_v, torch.from_numpy(new_slots).to(device), peer_O, peer_LSE, host_rows)
 
 
+# --------------------------------------------------------------------------- which outputs the oracle is asked for
+def sample_rows(rng, lo, hi, n_random, edges=(16, 32, 64, 128, 256)):
+    """Row indices in [lo, hi): first/last, tile edges +-1, plus random rows."""
+    rows = {lo, hi - 1}
+    for e in edges:
+        for base in range(lo, hi, e):
+            for d in (-1, 0, 1):
+                r = base + d
+                if lo <= r < hi:
+                    rows.add(r)
+            if len(rows) > 64:
+                break
+    rows = sorted(rows)
+    if len(rows) > 48:
+        keep = rng.choice(len(rows), 48, replace=False)
+        rows = sorted({rows[i] for i in keep} | {lo, hi - 1})
+    extra = rng.integers(lo, hi, n_random)
+    return np.unique(np.concatenate([np.asarray(rows, np.int64), extra.astype(np.int64)]))
+
+
+# (number of sampled (row, head) pairs, seed) of the full-size parity tests, per configuration; the benchmark's
+# CPU baseline times the oracle on the same samples
+PARITY_SAMPLES = {"C2-prefill": (2300, 102), "C4-prefill": (1045, 104), "C5-prefill": (2110, 105)}
+
+
+def prefill_parity_samples(pc: PrefillCase, n_total: int, seed: int):
+    """About n_total (row, head) pairs of a prefill case for a sampled comparison with the oracle: per request its
+    first and last row (in a striped layout the first one sees nothing in the later stripes: an empty visible set),
+    rows at multiples of 16 .. 256 and their neighbours, random rows; the heads cycle through all of them.
+    Returns (rows, heads, request of each row)."""
+    rng = np.random.default_rng(seed)
+    cu = host_i32(pc.cu_q)
+    rows, reqs = [], []
+    for r in range(pc.batch):
+        rr = sample_rows(rng, int(cu[r]), int(cu[r + 1]), max(8, n_total // pc.batch - 48))
+        rows.append(rr); reqs.append(np.full(len(rr), r))
+    rows, reqs = np.concatenate(rows), np.concatenate(reqs)
+    heads = (np.arange(len(rows)) * 7 + rng.integers(0, pc.Hq)) % pc.Hq
+    return rows.astype(np.int64), heads.astype(np.int64), reqs
+
+
 # --------------------------------------------------------------------------- the five configurations
 def config1_prefill(device, r_q_unused: int = 0) -> PrefillCase:
     """Tiny ESP step: 4 heads, query chunk 256 at positions 768..1023, two contiguous shards of 512."""

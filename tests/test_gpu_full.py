@@ -7,7 +7,7 @@ import pytest
 import torch
 
 import oracle
-from esp_checks import check_o_lse, sample_rows
+from esp_checks import check_o_lse
 from paper_2404_09526_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -23,28 +23,19 @@ def say(msg):
     print(f"[case] {msg}", flush=True)
 
 
-def prefill_samples(pc, n_random_per_req, seed):
-    rng = np.random.default_rng(seed)
-    cu = wl.host_i32(pc.cu_q)
-    rows, reqs = [], []
-    for r in range(pc.batch):
-        rr = sample_rows(rng, int(cu[r]), int(cu[r + 1]), n_random_per_req)
-        rows.append(rr); reqs.append(np.full(len(rr), r))
-    rows, reqs = np.concatenate(rows), np.concatenate(reqs)
-    heads = (np.arange(len(rows)) * 7 + rng.integers(0, pc.Hq)) % pc.Hq      # cycles through every head
-    return rows.astype(np.int64), heads.astype(np.int64), reqs
-
-
-def check_prefill_sampled(esp, pc, n_random_per_req, seed):
-    rows, heads, reqs = prefill_samples(pc, n_random_per_req, seed)
+def check_prefill_sampled(esp, pc, n_total, seed):
+    """The launch configuration bench.py times: one shard -> bf16 output; several shards -> fp32 partials, merged once."""
+    rows, heads, reqs = wl.prefill_parity_samples(pc, n_total, seed)
     assert set(heads.tolist()) == set(range(pc.Hq))
     qb, qp = wl.bits(pc.q), wl.host_i32(pc.q_pos)
     single = pc.batch == 1
+    several = len(pc.shards) > 1
+    ri, hi = torch.from_numpy(rows).to(pc.q.device), torch.from_numpy(heads).to(pc.q.device)
     parts, refs = [], []
     for si, s in enumerate(pc.shards):
         say(f"{pc.name} shard {si}: Tq={pc.Tq} Tkv={s.k.shape[0]} Hq={pc.Hq} Hkv={pc.Hkv} batch={pc.batch} samples={len(rows)}")
         # outputs start as NaN, so that the no-NaN check below also proves every row was written by this launch
-        O = torch.full_like(pc.q, float("nan"))
+        O = torch.full(pc.q.shape, float("nan"), dtype=torch.float32 if several else torch.bfloat16, device=pc.q.device)
         LSE = torch.full((pc.Tq, pc.Hq), float("nan"), dtype=torch.float32, device=pc.q.device)
         esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos,
                                      None if single else pc.cu_q, None if single else s.cu_kv,
@@ -54,56 +45,64 @@ def check_prefill_sampled(esp, pc, n_random_per_req, seed):
         cu_kv = wl.host_i32(s.cu_kv)
         Or, Lr = oracle.partial_attn(qb, wl.bits(s.k), wl.bits(s.v), qp, wl.host_i32(s.kv_pos), pc.scale, pc.causal,
                                      rows, heads, cu_kv[reqs], cu_kv[reqs + 1])
-        Og = O[torch.from_numpy(rows).to(O.device), torch.from_numpy(heads).to(O.device)].float().cpu().numpy()
-        Lg = LSE[torch.from_numpy(rows).to(O.device), torch.from_numpy(heads).to(O.device)].cpu().numpy()
-        st = check_o_lse(Og, Lg, Or, Lr, f"{pc.name} shard {si}")
-        say(f"  ok: {st}")
+        st = check_o_lse(O[ri, hi].float().cpu().numpy(), LSE[ri, hi].cpu().numpy(), Or, Lr, f"{pc.name} shard {si}")
+        say(f"  ok: {st}; rows with an empty visible set among the samples: {int(np.isneginf(Lr).sum())}")
         # properties that hold at any size: no NaN anywhere, LSE finite or -inf
-        assert not torch.isnan(O.float()).any() and not torch.isnan(LSE).any()
+        assert not torch.isnan(O).any() and not torch.isnan(LSE).any()
+        if several and si == len(pc.shards) - 1:
+            # the bf16 output of the same call at this size: the fp32 one rounded, bit for bit
+            Ob = torch.full_like(pc.q, float("nan")); Lb = torch.full_like(LSE, float("nan"))
+            esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos, None if single else pc.cu_q, None if single else s.cu_kv,
+                                         None if single else pc.max_q, None if single else s.max_kv, softmax_scale=pc.scale,
+                                         causal=pc.causal, O=Ob, LSE=Lb)
+            torch.cuda.synchronize()
+            assert torch.equal(Ob.view(torch.int16), O.to(torch.bfloat16).view(torch.int16)) and torch.equal(Lb.view(torch.int32), LSE.view(torch.int32))
+            del Ob, Lb
         parts.append((O, LSE)); refs.append((Or, Lr))
-    if len(parts) > 1:
+    if several:
         Om, Lm = esp.esp_merge_partials([p[0] for p in parts], [p[1] for p in parts])
         torch.cuda.synchronize()
         Oref, Lref = oracle.merge_partials(np.stack([r[0] for r in refs]), np.stack([r[1] for r in refs]))
-        ri, hi = torch.from_numpy(rows).to(Om.device), torch.from_numpy(heads).to(Om.device)
-        st = check_o_lse(Om[ri, hi].float().cpu().numpy(), Lm[ri, hi].cpu().numpy(), Oref, Lref, f"{pc.name} merged", roundings=2)
+        st = check_o_lse(Om[ri, hi].float().cpu().numpy(), Lm[ri, hi].cpu().numpy(), Oref, Lref, f"{pc.name} merged")
         say(f"  merged ok: {st}")
         # causal striped layout with r_q = 0: every row sees at least its own token in shard 0
-        assert torch.isfinite(Lm).all()
+        assert torch.isfinite(Lm).all() and not torch.isnan(Om.float()).any()
 
 
 def test_config2_prefill_striped_4_shards(esp, cuda):
     pc = wl.config2_prefill(cuda)
     assert pc.visible_pairs_per_head == 2 * 8192 * 8192 - 8192
-    check_prefill_sampled(esp, pc, 40, 102)
-    # stripe 0's first query sees nothing in shards 1..3 (kv positions 1, 2, 3 > 0)
+    check_prefill_sampled(esp, pc, *wl.PARITY_SAMPLES[pc.name])
 
 
 def test_config4_prefill_long_context(esp, cuda):
     pc = wl.config4_prefill(cuda)
     assert pc.visible_pairs_per_head == 32768 * 262144
-    check_prefill_sampled(esp, pc, 8, 104)
+    check_prefill_sampled(esp, pc, *wl.PARITY_SAMPLES[pc.name])
 
 
-@pytest.mark.parametrize("ticks", [None, "0"])
-def test_chunk_against_a_long_prefix_with_round_start_waits(esp, cuda, monkeypatch, ticks):
+@pytest.mark.parametrize("ticks", [None, 0])
+def test_chunk_against_a_long_prefix_with_round_start_waits(esp, cuda, ticks):
     """A 4096-token chunk against 32768 earlier tokens: long, alike items, so the workgroups that share a KV head wait
     for each other at the start of every dealt round.  Run as is, and with the longest wait set to nothing, so that
     every wait gives up at once (what a missing workgroup causes): the results must not depend on it."""
-    if ticks is not None:
-        monkeypatch.setenv("ESP_PREFILL_SYNC_TICKS", ticks)
-    pc = wl.contiguous_prefill("chunk-vs-prefix", 4096, 32768 - 4096, [(0, 32768)], 32, 32, 33, cuda)
-    check_prefill_sampled(esp, pc, 96, 7)
+    was = esp.esp_debug_set_prefill_sync_ticks(ticks) if ticks is not None else None
+    try:
+        pc = wl.contiguous_prefill("chunk-vs-prefix", 4096, 32768 - 4096, [(0, 32768)], 32, 32, 33, cuda)
+        check_prefill_sampled(esp, pc, 256, 7)
+    finally:
+        if was is not None:
+            esp.esp_debug_set_prefill_sync_ticks(was)
 
 
 def test_config5_prefill_varlen_gqa(esp, cuda):
     pc = wl.config5_prefill(cuda)
     assert pc.visible_pairs_per_head == 2994661376
-    check_prefill_sampled(esp, pc, 6, 105)
+    check_prefill_sampled(esp, pc, *wl.PARITY_SAMPLES[pc.name])
 
 
 def check_decode_sampled(esp, dc, sample, heads_per_req=None):
-    say(f"{dc.name}: B={dc.B} total={dc.total_tokens} max={int(dc.lens.max())} Hq={dc.Hq} Hkv={dc.Hkv} S={dc.num_slots} sample={sample}")
+    say(f"{dc.name}: B={dc.B} total={dc.total_tokens} max={int(dc.lens.max())} Hq={dc.Hq} Hkv={dc.Hkv} S={dc.num_slots} requests checked={len(sample)}")
     slots, off = wl.host_i32(dc.slot_idx), wl.host_i32(dc.seq_offsets)
     assert len(np.unique(slots)) == len(slots)                      # unique, non-contiguous slots
     kp = np.zeros((dc.num_slots, dc.Hkv, dc.D), np.uint16); vp = np.zeros_like(kp)   # lazily paged host image
@@ -144,26 +143,15 @@ def check_decode_sampled(esp, dc, sample, heads_per_req=None):
     assert sum_after[0] == sum_before[0] + added[0] and sum_after[1] == sum_before[1] + added[1]   # free slots were zero
 
 
-def pick_requests(lens, n):
-    order = np.argsort(lens)
-    picks = {int(order[0]), int(order[-1]), int(order[len(order) // 2])}
-    rng = np.random.default_rng(3)
-    while len(picks) < n:
-        picks.add(int(rng.integers(0, len(lens))))
-    return sorted(picks)
-
-
 def test_config3_decode_pool_4M_slots(esp, cuda):
-    lens = wl.lognormal_lengths(64, 8192, 1024, 131072, 2)
-    sample = pick_requests(lens, 10)
-    dc = wl.config3_decode(cuda, sample_reqs=sample)
+    """Every request, every head."""
+    dc = wl.config3_decode(cuda)
     assert dc.Hkv * dc.D * 2 * 2 == 16384                           # bytes per resident token (K and V rows)
-    check_decode_sampled(esp, dc, sample)
+    check_decode_sampled(esp, dc, list(range(dc.B)))
 
 
 def test_config5_decode_pool_16M_slots_gqa(esp, cuda):
-    lens = wl.lognormal_lengths(256, 16384, 512, 1 << 20, 4)
-    sample = pick_requests(lens, 10)
-    dc = wl.config5_decode(cuda, sample_reqs=sample)
-    check_decode_sampled(esp, dc, sample, heads_per_req=np.array([0, 5, 10, 15, 17, 22, 27, 28, 31], np.int64))
+    """Every request, nine query heads that cover all eight KV heads."""
+    dc = wl.config5_decode(cuda)
+    check_decode_sampled(esp, dc, list(range(dc.B)), heads_per_req=np.array([0, 5, 10, 15, 17, 22, 27, 28, 31], np.int64))
 

@@ -25,7 +25,11 @@ def say(msg):
 
 
 def run_prefill_case(esp, pc, check_merged=True, workspace=None):
-    """Runs every shard through the HIP path, checks each partial and the merged result."""
+    """Runs every shard through the HIP path, with bf16 and with fp32 partial outputs, and checks each partial.  With
+    several shards: the fp32 partials are merged and compared with the oracle's merge of ITS OWN fp64 partials, i.e.
+    with attention over the union of the shards (the pipeline: one rounding to bf16, at the end); the bf16 partials are
+    merged and compared with the oracle's merge of those very bf16 arrays (the merge kernel on its own).  Returns the
+    bf16 partials."""
     qb, qp = wl.bits(pc.q), wl.host_i32(pc.q_pos)
     cu_q = wl.host_i32(pc.cu_q)
     Tq, Hq, D = pc.q.shape
@@ -33,7 +37,7 @@ def run_prefill_case(esp, pc, check_merged=True, workspace=None):
     heads = np.tile(np.arange(Hq, dtype=np.int64), Tq)
     req_of_row = np.searchsorted(cu_q, np.arange(Tq), side="right") - 1
     single = pc.batch == 1
-    parts, refs = [], []
+    parts, parts32, refs = [], [], []
     for si, s in enumerate(pc.shards):
         say(f"{pc.name} shard {si}: Tq={Tq} Tkv={s.k.shape[0]} Hq={Hq} Hkv={pc.Hkv} batch={pc.batch} causal={pc.causal}")
         # outputs start as NaN: a row the launch never wrote cannot pass as a stale copy of an earlier result
@@ -50,14 +54,30 @@ def run_prefill_case(esp, pc, check_merged=True, workspace=None):
                                      rows, heads, lo, hi)
         check_o_lse(O.float().cpu().numpy().reshape(-1, D), LSE.cpu().numpy().reshape(-1), Or, Lr,
                     f"{pc.name} shard {si}")
-        parts.append((O, LSE)); refs.append((Or, Lr))
+        O32 = torch.full(pc.q.shape, float("nan"), dtype=torch.float32, device=pc.q.device)
+        LSE32 = torch.full_like(LSE, float("nan"))
+        esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos,
+                                     None if single else pc.cu_q, None if single else s.cu_kv,
+                                     None if single else pc.max_q, None if single else s.max_kv,
+                                     softmax_scale=pc.scale, causal=pc.causal, O=O32, LSE=LSE32, workspace=workspace)
+        torch.cuda.synchronize()
+        check_o_lse(O32.cpu().numpy().reshape(-1, D), LSE32.cpu().numpy().reshape(-1), Or, Lr, f"{pc.name} shard {si} (fp32 out)")
+        # the two output types differ by the final rounding only
+        assert torch.equal(O32.to(torch.bfloat16).view(torch.int16), O.view(torch.int16)) and torch.equal(LSE32.view(torch.int32), LSE.view(torch.int32))
+        parts.append((O, LSE)); parts32.append((O32, LSE32)); refs.append((Or, Lr))
     if check_merged and len(parts) > 1:
         say(f"{pc.name} merge of {len(parts)} partials")
-        Om, Lm = esp.esp_merge_partials([p[0] for p in parts], [p[1] for p in parts])
+        Om, Lm = esp.esp_merge_partials([p[0] for p in parts32], [p[1] for p in parts32])
         torch.cuda.synchronize()
         # pipeline check: the oracle merges ITS OWN fp64 partials = attention over the union of the shards
         Oref, Lref = oracle.merge_partials(np.stack([r[0] for r in refs]), np.stack([r[1] for r in refs]))
-        check_o_lse(Om.float().cpu().numpy().reshape(-1, D), Lm.cpu().numpy().reshape(-1), Oref, Lref, f"{pc.name} merged", roundings=2)
+        check_o_lse(Om.float().cpu().numpy().reshape(-1, D), Lm.cpu().numpy().reshape(-1), Oref, Lref, f"{pc.name} merged")
+        # merge kernel on bf16 partials: against the oracle's merge of the very arrays the GPU merged
+        Ob, Lb = esp.esp_merge_partials([p[0] for p in parts], [p[1] for p in parts])
+        torch.cuda.synchronize()
+        Oref, Lref = oracle.merge_partials(np.stack([oracle.bf16_bits_to_f64(wl.bits(p[0])).reshape(-1, D) for p in parts]),
+                                           np.stack([p[1].cpu().numpy().astype(np.float64).reshape(-1) for p in parts]))
+        check_o_lse(Ob.float().cpu().numpy().reshape(-1, D), Lb.cpu().numpy().reshape(-1), Oref, Lref, f"{pc.name} merge of bf16 partials")
     return parts
 
 
@@ -71,7 +91,8 @@ def test_config1_prefill_exhaustive(esp, cuda):
 def test_config1_merged_equals_unpartitioned_attention(esp, cuda):
     """The GPU pipeline (2 partials -> merge) against the oracle run directly on the whole 1024-token KV."""
     pc = wl.config1_prefill(cuda)
-    parts = [esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos, softmax_scale=pc.scale) for s in pc.shards]
+    parts = [esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos, softmax_scale=pc.scale, out_dtype=torch.float32)
+             for s in pc.shards]
     Om, Lm = esp.esp_merge_partials([p[0] for p in parts], [p[1] for p in parts])
     torch.cuda.synchronize()
     k_all = np.concatenate([wl.bits(s.k) for s in pc.shards]); v_all = np.concatenate([wl.bits(s.v) for s in pc.shards])
@@ -302,6 +323,27 @@ def test_prefill_large_scores_refresh_the_softmax_offset(esp, cuda):
     run_prefill_case(esp, pc2)
 
 
+@pytest.mark.parametrize("late_keys", [((300, 1.5),), ((523, 1.5),), ((300, 1.5), (523, 2.5), (1004, 3.5))])
+def test_prefill_offset_moves_for_the_whole_row_when_one_half_sees_the_large_key(esp, cuda, late_keys):
+    """A query row is held by two lanes, each with half of a tile's keys (key index % 8 < 4 in one, >= 4 in the
+    other).  A late key whose score lies 2^36 above everything before it makes the probability sum of ITS half
+    exceed the limit that moves the softmax offset, while the other half's sum stays small: the offset, and
+    everything rescaled with it, must still move for the whole row.  Nothing here leaves the range of the
+    optimistic pass (every tile sum stays below 2^100 of the offset in use), so the pipelined path itself is what
+    is compared with the oracle, not the exact re-sweep.  Keys 300 and 1004 fall into one half, 523 into the other;
+    with all three the offset moves three times (by 36, 25 and 25 bits)."""
+    Tq, Tkv = 300, 1100
+    pc = wl.contiguous_prefill("half-row-offset", Tq, 2000, [(0, Tkv)], 4, 2, 43, cuda, causal=False)
+    s = pc.shards[0]
+    u = torch.ones(pc.D, dtype=torch.bfloat16, device=cuda)
+    pc.q[:] = (pc.q.float() * 0.05 + 1.5).to(torch.bfloat16)      # every row close to 1.5 * u
+    s.k[:] = (s.k.float() * 0.05).to(torch.bfloat16)              # scores near 0 ...
+    for idx, c in late_keys:
+        s.k[idx] = c * u                                           # ... but for these: 1.5 * c * 128 * scale = 17 c nats
+    assert [i % 8 >= 4 for i, _ in late_keys] in ([True], [False], [True, False, True])
+    run_prefill_case(esp, pc)
+
+
 @pytest.mark.gpu
 @pytest.mark.parametrize("causal", [False, True])
 def test_prefill_scores_beyond_the_optimistic_range_take_the_exact_sweep(esp, cuda, causal):
@@ -338,12 +380,19 @@ def test_prefill_more_items_than_workgroups(esp, cuda, Hq, Hkv):
     run_prefill_case(esp, pc)
 
 
-def test_debug_validation_of_index_arrays(esp, cuda, monkeypatch):
-    """ESP_DEBUG_VALIDATE=1: slots outside the pool, slots named twice, offsets that decrease or do not end at the row
+def test_debug_validation_of_index_arrays(esp, cuda):
+    """esp_debug_set_validate(1) (what ESP_DEBUG_VALIDATE=1 in the environment sets at load time): slots outside the pool, slots named twice, offsets that decrease or do not end at the row
     count are refused with ESP_ERR_INVALID_ARG before anything is launched; sound arrays pass and give the usual result."""
-    monkeypatch.setenv("ESP_DEBUG_VALIDATE", "1")
     dc = wl.config1_decode(cuda)
     max_len = int(dc.lens.max())
+    was = esp.esp_debug_set_validate(True)
+    try:
+        _validation_cases(esp, cuda, dc, max_len)
+    finally:
+        esp.esp_debug_set_validate(was)
+
+
+def _validation_cases(esp, cuda, dc, max_len):
     O, L = esp.esp_partial_attn_decode(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, max_len, softmax_scale=dc.scale)
     bad = dc.slot_idx.clone(); bad[17] = dc.num_slots
     with pytest.raises(esp.EspError) as e:
@@ -378,7 +427,7 @@ def test_debug_validation_of_index_arrays(esp, cuda, monkeypatch):
     with pytest.raises(esp.EspError):
         esp.esp_partial_attn_prefill(pc.q, s0.k, s0.v, pc.q_pos, s0.kv_pos, pc.cu_q, short, pc.max_q, s0.max_kv, softmax_scale=pc.scale)
     torch.cuda.synchronize()
-    monkeypatch.delenv("ESP_DEBUG_VALIDATE")
+    esp.esp_debug_set_validate(False)
     O2, L2 = esp.esp_partial_attn_decode(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, max_len, softmax_scale=dc.scale)
     torch.cuda.synchronize()
     assert torch.equal(O, O2) and torch.equal(L, L2)
