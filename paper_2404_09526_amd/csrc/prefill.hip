@@ -408,7 +408,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     // accepted without a move, -1 while the row has not seen a key yet (m_use is then a stand-in 0).
     float m_use = 0.f, lim = -1.f;
     float lsum = 0.f;          // running sum of exp2 over this lane's half of the keys (for the log-sum-exp)
-    float lsum_r = 0.f;        // the same sum over the probabilities as rounded to bf16 (what O^T accumulates)
+    float lcorr = 0.f;         // what rounding the probabilities to bf16 added to that sum, over the tiles that track it
     float psum = 0.f, psum_r = 0.f, p0 = 0.f, p1 = 0.f;
 
     floatx16 sbuf[2][2];       // S^T of two tiles in flight: [tile parity][kvb]
@@ -457,21 +457,30 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
 
     // probabilities of score pair c (0..15) of the current tile, in two parts placed behind the two MFMAs of a
     // step: exp2 first, then the fp32 partial sum (of the unrounded values: the log-sum-exp has to be good to
-    // 1e-4), the bf16 pack, and the sum of the packed values (one dot product with (1, 1)).  O is normalised by
-    // the latter: then it is a convex combination of value rows whatever the rounding of the weights did, a
-    // rounding error common to the weights cancels, and a row that sees a single key returns that row exactly.
+    // 1e-4) and the bf16 pack.  O^T accumulates the ROUNDED probabilities, so O is best normalised by their sum:
+    // then it is a convex combination of value rows whatever the rounding did, an error common to the weights
+    // cancels, and a row that sees a single key returns that key's value row exactly.  Summing the packed values
+    // too (one dot product with (1, 1) per pair) costs 4 % of the loop's issue slots, though, and matters only
+    // where few keys carry a row: so `track` is set in the masked iterations around the diagonal (a row with
+    // fewer than 64 keys has no other) and in the exact sweep, and a tile at which the offset moves (a late,
+    // dominant key) is accounted for in close_tile.  The plain iterations sum the unrounded values only.
     auto pair_exp = [&](const floatx16 (&sc)[2], int c) {
         const int kvb = c >> 3, r = 2 * (c & 7);
         p0 = __builtin_amdgcn_exp2f(fmaf(sc[kvb][r], a.scale_log2, -m_use));
         p1 = __builtin_amdgcn_exp2f(fmaf(sc[kvb][r + 1], a.scale_log2, -m_use));
     };
-    auto pair_sum_pack = [&](int c) {
+    auto packed_sum = [](uint32_t pk, float acc) {            // acc + both bf16 halves of pk
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc, false);
+    };
+    auto pair_sum_pack = [&](int c, bool track) {
         if (c == 0) psum = p0 + p1;
         else { psum += p0; psum += p1; }
         const uint32_t pk = pack_bf16(p0, p1);
-        psum_r = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), __builtin_bit_cast(bf16x2, 0x3f803f80u),
-                                                 c == 0 ? 0.f : psum_r, false);
-        asm volatile("" :: "v"(pk), "v"(psum), "v"(psum_r));   // sums and pack here, not in a bunch further down
+        if (track) {
+            psum_r = packed_sum(pk, c == 0 ? 0.f : psum_r);
+            asm volatile("" :: "v"(psum_r));
+        }
+        asm volatile("" :: "v"(pk), "v"(psum));   // sum and pack here, not in a bunch further down
         pf[c >> 3][(c >> 2) & 1].u[c & 3] = pk;
     };
 
@@ -484,9 +493,9 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     // stand-in offset, means the optimistic pass cannot be trusted: the workgroup then redoes its rows with the
     // plain sweep below (`unsafe` is only ever set, never cleared).
     int32_t* lds_unsafe = (int32_t*)(smem + kLdsFlag);
-    auto close_tile = [&](const floatx16 (&sc)[2]) {
+    auto close_tile = [&](const floatx16 (&sc)[2], bool tracked) {
         lsum += psum;
-        lsum_r += psum_r;
+        if (tracked) lcorr += psum_r - psum;
         if (__builtin_amdgcn_ballot_w64(!(psum <= lim)) != 0) {
             const float tm = row_max(sc);
             // A query row is held by two lanes (l and l | 32), each with the sum over its half of the tile's keys:
@@ -497,12 +506,21 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
             const bool move = rows >= 1.f && tm != -INFINITY;        // a fresh row whose tile is all masked stays fresh
             const bool bad = move && (rows >= 3.f || (lim < 0.f && !(fabsf(tm) <= 64.f)));
             if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0) *lds_unsafe = 1;
+            if (!tracked) {
+                // a tile whose rounded sum was not kept: its packed probabilities are all still in pf (the next
+                // tile has not begun to overwrite them), so the sum is taken here; rows that stay where they are
+                // have nothing dominant in this tile and go without
+                float d = 0.f;
+#pragma unroll
+                for (int c = 0; c < 16; ++c) d = packed_sum(pf[c >> 3][(c >> 2) & 1].u[c & 3], d);
+                if (move) lcorr += d - psum;
+            }
             const float m_new = move ? m_use + ceilf(tm - m_use) : m_use;     // whole steps: alpha is a power of two
             const float alpha = __builtin_amdgcn_exp2f(m_use - m_new);        // 1 where nothing moves
             m_use = m_new;
             if (move) lim = kSumLimit;
             lsum *= alpha;
-            lsum_r *= alpha;
+            lcorr *= alpha;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -563,7 +581,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
             // V^T fragment too (LDS reads return in order) and one wait per step is enough
             read_v(m & 1, (m < 2 ? ST3 : ST) * kTileBytes, (m + 14) & 15);
             read_k(m & 1, m + 2 < 16 ? ST1 : ST2, (m + 2) & 15);
-            pair_sum_pack(m);
+            pair_sum_pack(m, !PLAIN);
             // the transfers of this iteration, spread out (a burst from all wavefronts at once backs up the memory
             // pipeline); the odd ones of wavefronts 7 and 0 go first, so that "all but the last four have landed"
             // is the same wait for every wavefront
@@ -575,7 +593,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
             if (do_v && (m == 9 || m == 12)) fetch_v_part(v_next, p_next, ST2, tail_v, m / 12);
             __builtin_amdgcn_sched_barrier(0);
         }
-        close_tile(sc);
+        close_tile(sc, !PLAIN);
         k_next += tile_bytes; v_next += tile_bytes; p_next += kBN;
         // what iteration j-1 fetched must have landed; this iteration's own transfers may stay in flight
         if (do_k) wait_vm<4>();
@@ -684,7 +702,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     if (__builtin_amdgcn_readfirstlane(*lds_unsafe) != 0) {
         float m_ref = -INFINITY;
         lsum = 0.f;
-        lsum_r = 0.f;
+        lcorr = 0.f;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -712,16 +730,16 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
             const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_ref - m_new);
             m_ref = m_new;
             lsum *= alpha;
-            lsum_r *= alpha;
+            lcorr *= alpha;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
             m_use = (m_ref == -INFINITY) ? 0.f : m_ref;             // nothing visible yet: exp2(-inf - 0) = 0
 #pragma unroll
-            for (int c = 0; c < 16; ++c) { pair_exp(sc, c); pair_sum_pack(c); }
+            for (int c = 0; c < 16; ++c) { pair_exp(sc, c); pair_sum_pack(c, true); }
             lsum += psum;
-            lsum_r += psum_r;
+            lcorr += psum_r - psum;
 #pragma unroll
             for (int p = 0; p < 16; ++p) {
                 read_v(0, 0, p);
@@ -734,7 +752,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
 
     // ---- epilogue: normalise, write O (bf16) and LSE (natural log)
     const float ltot = half_swap_sum(lsum);
-    const float ltot_r = half_swap_sum(lsum_r);
+    const float ltot_r = half_swap_sum(lsum + lcorr);
     const float inv = ltot_r > 0.f ? 1.0f / ltot_r : 0.f;
     // O goes through LDS so that it leaves in whole rows: a lane holds 8-byte pieces of one row, 16 of them spread
     // over the 256 bytes; written to a wavefront-private 32 x 272-byte block (the K stages are free by now: the
