@@ -146,6 +146,26 @@ size_t esp_decode_workspace_bytes(int32_t B, int32_t total_tokens, int32_t max_l
                                   int32_t Hq, int32_t Hkv, int32_t D);
 
 /*
+ * esp_partial_attn_decode for callers that cannot allocate or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, results and kernels, minus the workspace:
+ * the split-K partials go to a block of ESP_DECODE_STATIC_SCRATCH_BYTES of
+ * device memory built into the library (each GPU the library runs on holds it
+ * until the process ends).  The call allocates and frees nothing.  A call whose
+ * esp_decode_workspace_bytes(...) exceeds the block returns ESP_ERR_WORKSPACE.
+ * All calls on one GPU share the block: calls that may overlap in time on one
+ * GPU (two streams, two threads) race and must use esp_partial_attn_decode
+ * with a workspace each.  Nothing in the block has to be cleared between calls.
+ */
+#define ESP_DECODE_STATIC_SCRATCH_BYTES (32u << 20)
+esp_status esp_partial_attn_decode_static(
+    const void* q, const void* k_pool, const void* v_pool, int64_t num_slots,
+    const int32_t* slot_idx, const int32_t* seq_offsets, int32_t B,
+    int32_t total_tokens, int32_t max_len,
+    int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale,
+    void* O, float* LSE, void* stream);
+
+/*
  * Combination of partial results ("generate the final output", Sec. 2.3;
  * results "sent back to the master", Sec. 4.2).  For each (token, head):
  *   m = max_p LSE_p,  w_p = exp(LSE_p - m),

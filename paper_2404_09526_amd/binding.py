@@ -26,7 +26,9 @@ EXPORTS = (
     "esp_probe_mfma_bf16", "esp_probe_stream_read",
     "esp_partial_attn_prefill_f32", "esp_merge_partials_f32",
     "esp_debug_set_validate", "esp_debug_set_prefill_sync_ticks",
+    "esp_partial_attn_decode_static",
 )
+ESP_DECODE_STATIC_SCRATCH_BYTES = 32 << 20
 
 
 class EspError(RuntimeError):
@@ -56,6 +58,8 @@ def _load() -> ctypes.CDLL:
     L.esp_prefill_workspace_bytes.restype = sz
     L.esp_partial_attn_decode.argtypes = [vp, vp, vp, i64, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, vp, vp, sz, vp]
     L.esp_partial_attn_decode.restype = i32
+    L.esp_partial_attn_decode_static.argtypes = [vp, vp, vp, i64, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, vp, vp]
+    L.esp_partial_attn_decode_static.restype = i32
     L.esp_decode_workspace_bytes.argtypes = [i32] * 6
     L.esp_decode_workspace_bytes.restype = sz
     L.esp_merge_partials.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp]
@@ -205,6 +209,28 @@ def esp_partial_attn_decode(q, k_pool, v_pool, slot_idx, seq_offsets, max_len, s
     _check(lib.esp_partial_attn_decode(_ptr(q), _ptr(k_pool), _ptr(v_pool), S, _ptr(slot_idx), _ptr(seq_offsets), B,
                                        total, int(max_len), Hq, Hkv, D, float(softmax_scale), _ptr(O), _ptr(LSE),
                                        _ptr(workspace), workspace.numel(), _stream()))
+    return O, LSE
+
+
+def esp_partial_attn_decode_static(q, k_pool, v_pool, slot_idx, seq_offsets, max_len, softmax_scale=None, O=None, LSE=None):
+    """esp_partial_attn_decode on the library's built-in scratch block: the call itself allocates nothing (O and LSE
+    must be given for that to hold on this side too)."""
+    _dev(q, torch.bfloat16, "q"); _dev(k_pool, torch.bfloat16, "k_pool"); _dev(v_pool, torch.bfloat16, "v_pool")
+    _dev(slot_idx, torch.int32, "slot_idx"); _dev(seq_offsets, torch.int32, "seq_offsets")
+    B, Hq, D = q.shape
+    S, Hkv, Dk = k_pool.shape
+    if v_pool.shape != k_pool.shape or Dk != D or seq_offsets.numel() != B + 1:
+        raise ValueError("decode: shape mismatch")
+    if softmax_scale is None:
+        softmax_scale = D ** -0.5
+    if O is None:
+        O = torch.empty_like(q)
+    if LSE is None:
+        LSE = torch.empty((B, Hq), dtype=torch.float32, device=q.device)
+    _dev(O, torch.bfloat16, "O"); _dev(LSE, torch.float32, "LSE")
+    _check(lib.esp_partial_attn_decode_static(_ptr(q), _ptr(k_pool), _ptr(v_pool), S, _ptr(slot_idx), _ptr(seq_offsets), B,
+                                              slot_idx.numel(), int(max_len), Hq, Hkv, D, float(softmax_scale), _ptr(O), _ptr(LSE),
+                                              _stream()))
     return O, LSE
 
 

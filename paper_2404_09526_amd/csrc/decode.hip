@@ -13,9 +13,37 @@
 //   * dot products on the vector ALU with a 16-lane butterfly per head, online softmax in
 //     the exp2 domain per batch of tokens, fp32 accumulation;
 //   * a second kernel combines the partials of each (request, head) and writes O, LSE.
+#include <mutex>
+
 #include "esp_common.h"
 
 namespace esp {
+
+// Split-K partials of the entry point that allocates nothing: a fixed block of device memory that every GPU the
+// library runs on holds until the process ends.  In host code the array's name is only a stand-in; its device
+// address is asked for once per device (static_scratch below) and that pointer is what the kernels are given.
+static __device__ __align__(256) unsigned char scratch[ESP_DECODE_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (looked up on the first call on that device).
+static esp_status static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return fail(ESP_ERR_HIP, "decode (static scratch): cannot identify the current device");
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || p == nullptr)
+            return fail(ESP_ERR_HIP, "decode (static scratch): hipGetSymbolAddress failed on device %d: %s", dev, hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return ESP_OK;
+}
 
 constexpr int kDecWaves = 8;         // wavefronts per workgroup
 constexpr int kDecTB = 4;            // tokens per wavefront per loop step
@@ -237,6 +265,20 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(const int32_t* __re
         O[((int64_t)b * Hq + h) * (kHeadDim / 2) + dp] = pack_bf16(o0, o1);
         if (dp == 0) LSE[(int64_t)b * Hq + h] = (mx == -INFINITY) ? -INFINITY : (mx + __builtin_amdgcn_logf(Lt)) * kLn2;
     }
+}
+
+esp_status launch_decode_static(const void* q, const void* k_pool, const void* v_pool, const int32_t* slot_idx,
+                                const int32_t* seq_offsets, int32_t B, int32_t total_tokens, int32_t Hq, int32_t Hkv,
+                                float softmax_scale, void* O, float* LSE, hipStream_t stream) {
+    const size_t need = decode_workspace_bytes(B, total_tokens, Hq, Hkv);
+    if (need > (size_t)ESP_DECODE_STATIC_SCRATCH_BYTES)
+        return fail(ESP_ERR_WORKSPACE, "decode (static scratch): this call needs %zu bytes of scratch memory, the built-in block holds %zu; "
+                    "use esp_partial_attn_decode with a workspace", need, (size_t)ESP_DECODE_STATIC_SCRATCH_BYTES);
+    void* ws = nullptr;
+    const esp_status st = static_scratch(&ws);
+    if (st != ESP_OK) return st;
+    return launch_decode(q, k_pool, v_pool, slot_idx, seq_offsets, B, total_tokens, Hq, Hkv, softmax_scale, O, LSE, ws,
+                         (size_t)ESP_DECODE_STATIC_SCRATCH_BYTES, stream);
 }
 
 esp_status launch_decode(const void* q, const void* k_pool, const void* v_pool, const int32_t* slot_idx,

@@ -30,6 +30,12 @@ esp_status check_launch(const char* what) {
 }
 
 static bool heads_ok(int32_t Hq, int32_t Hkv) { return Hq > 0 && Hkv > 0 && Hq % Hkv == 0; }
+// head counts the decode kernel covers
+static bool decode_heads_supported(int32_t Hq, int32_t Hkv) {
+    if (!heads_ok(Hq, Hkv)) return false;
+    const int G = Hq / Hkv;
+    return (Hkv == 4 || Hkv == 8 || Hkv == 16 || Hkv % 32 == 0) && (G == 1 || G == 2 || G == 4 || G == 8);
+}
 
 // ESP_DEBUG_VALIDATE=1 in the environment: the content of the device index arrays, trusted otherwise, is checked on
 // the host before the launch.  A debugging aid: it waits for the stream and copies the arrays back.
@@ -92,7 +98,7 @@ size_t esp_prefill_workspace_bytes(int32_t Tq, int32_t Tkv, int32_t batch, int32
 size_t esp_decode_workspace_bytes(int32_t B, int32_t total_tokens, int32_t max_len, int32_t Hq, int32_t Hkv,
                                   int32_t D) {
     (void)max_len;
-    if (B < 0 || total_tokens < 0 || !heads_ok(Hq, Hkv) || D != kHeadDim) return 0;
+    if (B < 0 || total_tokens < 0 || !decode_heads_supported(Hq, Hkv) || D != kHeadDim) return 0;   // 0: the call would be refused
     return decode_workspace_bytes(B, total_tokens, Hq, Hkv);
 }
 
@@ -200,36 +206,64 @@ esp_status esp_partial_attn_prefill_pool(const void* q, const void* k_pool, cons
                                     softmax_scale, causal, O, LSE, ws + 2 * stage, workspace_bytes - 2 * stage, stream);
 }
 
-esp_status esp_partial_attn_decode(const void* q, const void* k_pool, const void* v_pool, int64_t num_slots,
-                                   const int32_t* slot_idx, const int32_t* seq_offsets, int32_t B,
-                                   int32_t total_tokens, int32_t max_len, int32_t Hq, int32_t Hkv, int32_t D,
-                                   float softmax_scale, void* O, float* LSE, void* workspace,
-                                   size_t workspace_bytes, void* stream) {
+// argument checks common to the two decode entry points; *done is set when there is nothing to launch
+static esp_status decode_check(const void* q, const void* k_pool, const void* v_pool, int64_t num_slots, const int32_t* slot_idx,
+                               const int32_t* seq_offsets, int32_t B, int32_t total_tokens, int32_t max_len, int32_t Hq,
+                               int32_t Hkv, int32_t D, float softmax_scale, const void* O, const float* LSE, bool* done) {
+    *done = false;
     if (B < 0 || total_tokens < 0 || max_len < 0 || num_slots < 0)
         return fail(ESP_ERR_INVALID_ARG, "decode: negative size");
     if (!heads_ok(Hq, Hkv)) return fail(ESP_ERR_INVALID_ARG, "decode: Hq=%d must be a positive multiple of Hkv=%d", Hq, Hkv);
     if (D != kHeadDim) return fail(ESP_ERR_UNSUPPORTED, "decode: head_dim %d unsupported (only 128)", D);
     if (max_len > total_tokens) return fail(ESP_ERR_INVALID_ARG, "decode: max_len exceeds total_tokens");
-    if (B == 0) return ESP_OK;
+    if (B == 0) { *done = true; return ESP_OK; }
     if (!q || !O || !LSE || !seq_offsets) return fail(ESP_ERR_INVALID_ARG, "decode: null q/seq_offsets/O/LSE");
     if (total_tokens > 0 && (!k_pool || !v_pool || !slot_idx || num_slots == 0))
         return fail(ESP_ERR_INVALID_ARG, "decode: null pool/slot_idx");
     if (!(softmax_scale == softmax_scale) || softmax_scale < 0.f) return fail(ESP_ERR_INVALID_ARG, "decode: bad softmax_scale");
-    if (Hkv % 4 != 0 || !(Hkv == 4 || Hkv == 8 || Hkv == 16 || Hkv % 32 == 0))
-        return fail(ESP_ERR_UNSUPPORTED, "decode: Hkv=%d unsupported (4, 8, 16 or a multiple of 32)", Hkv);
-    int G = Hq / Hkv;
-    if (!(G == 1 || G == 2 || G == 4 || G == 8)) return fail(ESP_ERR_UNSUPPORTED, "decode: Hq/Hkv=%d unsupported (1, 2, 4, 8)", G);
+    if (!decode_heads_supported(Hq, Hkv))
+        return fail(ESP_ERR_UNSUPPORTED, "decode: Hq=%d, Hkv=%d unsupported (Hkv 4, 8, 16 or a multiple of 32; Hq/Hkv 1, 2, 4 or 8)", Hq, Hkv);
+    return ESP_OK;
+}
+static esp_status decode_validate(const int32_t* slot_idx, const int32_t* seq_offsets, int32_t B, int32_t total_tokens, int32_t max_len,
+                                  int64_t num_slots, void* stream) {
+    if (!debug_validate()) return ESP_OK;
+    esp_status st = check_offsets("decode: seq_offsets", seq_offsets, B, total_tokens, max_len, (hipStream_t)stream);
+    if (st == ESP_OK) st = check_slots("decode", slot_idx, total_tokens, num_slots, false, false, (hipStream_t)stream);
+    return st;
+}
+
+esp_status esp_partial_attn_decode(const void* q, const void* k_pool, const void* v_pool, int64_t num_slots,
+                                   const int32_t* slot_idx, const int32_t* seq_offsets, int32_t B,
+                                   int32_t total_tokens, int32_t max_len, int32_t Hq, int32_t Hkv, int32_t D,
+                                   float softmax_scale, void* O, float* LSE, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
+    bool done;
+    esp_status st = decode_check(q, k_pool, v_pool, num_slots, slot_idx, seq_offsets, B, total_tokens, max_len, Hq, Hkv, D,
+                                 softmax_scale, O, LSE, &done);
+    if (st != ESP_OK || done) return st;
     size_t need = decode_workspace_bytes(B, total_tokens, Hq, Hkv);
     if (!workspace || workspace_bytes < need)
         return fail(ESP_ERR_WORKSPACE, "decode: workspace needs %zu bytes, got %zu", need, workspace ? workspace_bytes : (size_t)0);
     if ((uintptr_t)workspace & 255) return fail(ESP_ERR_WORKSPACE, "decode: workspace not 256-byte aligned");
-    if (debug_validate()) {
-        esp_status st = check_offsets("decode: seq_offsets", seq_offsets, B, total_tokens, max_len, (hipStream_t)stream);
-        if (st == ESP_OK) st = check_slots("decode", slot_idx, total_tokens, num_slots, false, false, (hipStream_t)stream);
-        if (st != ESP_OK) return st;
-    }
+    st = decode_validate(slot_idx, seq_offsets, B, total_tokens, max_len, num_slots, stream);
+    if (st != ESP_OK) return st;
     return launch_decode(q, k_pool, v_pool, slot_idx, seq_offsets, B, total_tokens, Hq, Hkv, softmax_scale, O, LSE,
                          workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+esp_status esp_partial_attn_decode_static(const void* q, const void* k_pool, const void* v_pool, int64_t num_slots,
+                                          const int32_t* slot_idx, const int32_t* seq_offsets, int32_t B,
+                                          int32_t total_tokens, int32_t max_len, int32_t Hq, int32_t Hkv, int32_t D,
+                                          float softmax_scale, void* O, float* LSE, void* stream) {
+    bool done;
+    esp_status st = decode_check(q, k_pool, v_pool, num_slots, slot_idx, seq_offsets, B, total_tokens, max_len, Hq, Hkv, D,
+                                 softmax_scale, O, LSE, &done);
+    if (st != ESP_OK || done) return st;
+    st = decode_validate(slot_idx, seq_offsets, B, total_tokens, max_len, num_slots, stream);
+    if (st != ESP_OK) return st;
+    return launch_decode_static(q, k_pool, v_pool, slot_idx, seq_offsets, B, total_tokens, Hq, Hkv, softmax_scale, O, LSE,
+                                (hipStream_t)stream);
 }
 
 static esp_status merge_entry(const void* const* O_parts, const float* const* LSE_parts, int32_t P, int32_t T,

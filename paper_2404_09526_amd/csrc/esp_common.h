@@ -57,6 +57,10 @@ esp_status launch_decode(const void* q, const void* k_pool, const void* v_pool, 
                          hipStream_t stream);
 
 int32_t set_prefill_sync_ticks(int32_t ticks);   // returns the previous value; negative restores the built-in default
+esp_status launch_decode_static(const void* q, const void* k_pool, const void* v_pool, const int32_t* slot_idx,
+                                const int32_t* seq_offsets, int32_t B, int32_t total_tokens, int32_t Hq, int32_t Hkv,
+                                float softmax_scale, void* O, float* LSE, hipStream_t stream);
+
 size_t prefill_workspace_bytes(int32_t Tq, int32_t Tkv, int32_t batch, int32_t Hq, int32_t Hkv);
 esp_status launch_prefill(const void* q, const void* k, const void* v, const int32_t* q_pos, const int32_t* kv_pos,
                           const int32_t* cu_q, const int32_t* cu_kv, int32_t batch, int32_t Tq, int32_t Tkv,
