@@ -256,7 +256,7 @@ esp_status esp_probe_mfma_bf16(const void* operands, int64_t operand_bytes, int3
 esp_status esp_probe_stream_read(const void* src, int64_t bytes, void* sink, void* stream);
 
 /*
- * Prefill batching plan (Sec. 5.4 "Batching", the dynamic program over sorted requests and sorted elastic
+ * Prefill batching plan (Sec. 5.3 "Batching", the dynamic program over sorted requests and sorted elastic
  * instances) -- host code, no GPU work; every pointer is HOST memory.
  *
  * Requests are given longest first (req_len[0] >= req_len[1] >= ... >= 1 tokens), instances in the scheduler's
@@ -276,7 +276,7 @@ esp_status esp_plan_prefill_batches(
     int32_t* split_req, int32_t* split_ins);
 
 /*
- * Iteration-time model of the prefill phase (Sec. 5.6 "Analytical model based on SIB"):
+ * Iteration-time model of the prefill phase (Sec. 5.5 "Optimizations", analytical model based on SIB, Eq. 7):
  *   T(R) = alpha + beta * sum_{r in R} len_r + gamma * sum_{r in R} len_r^2,
  * fitted by least squares to n >= 3 profiled batches (HOST arrays: per batch the two sums and the measured
  * time).  weights: NULL, or n non-negative factors; sample i's equation is multiplied by weights[i] before the

@@ -1,7 +1,7 @@
 """Oracle for the prefill batching plan and the iteration-time model -- TEST INFRASTRUCTURE ONLY.
 
-LoongServe (arXiv 2404.09526), Sec. 5.4 "Batching" (the dynamic program over sorted requests and sorted
-elastic instances) and Sec. 5.6 "Analytical model based on SIB" (iteration time = alpha + beta * sum(len)
+LoongServe (arXiv 2404.09526), Sec. 5.3 "Batching" (the dynamic program over sorted requests and sorted
+elastic instances) and Sec. 5.5 "Optimizations", analytical model based on SIB, Eq. 7 (iteration time = alpha + beta * sum(len)
 + gamma * sum(len^2), fitted by least squares).  Plain statements, written for checking by eye:
 
   * ``brute_force_plan`` enumerates EVERY way of cutting the request sequence and a prefix of the instance
@@ -12,12 +12,12 @@ elastic instances) and Sec. 5.6 "Analytical model based on SIB" (iteration time 
 Readings of the paper taken here (it leaves them open):
   * a batch's term T(R[j,i], E[l,k]) is the sum, over the requests of the batch, of the batch's iteration
     time divided by the request's input length (the "input latency" the section minimises is per input
-    token, as in the gain / cost formulas of Sec. 5.2 and 5.3); the iteration time is the model of Sec. 5.6
+    token, as in the gain / cost formulas of Sec. 5.1 and 5.2); the iteration time is the model of Sec. 5.5
     with the coefficients of the batch's degree of parallelism (its number of instances);
   * batches take consecutive requests and consecutive instances, both from the front; instances left over at
     the end stay unused (the minimum over the second index in the text);
   * D[j,i] <= V[l,k]: the tokens of the batch must fit the unused slots of its instances;
-  * "trained by the least square method" (Sec. 5.6) says nothing about weighting: the fit takes optional
+  * "trained by the least square method" (Sec. 5.5) says nothing about weighting: the fit takes optional
     per-sample weights; unweighted is the default.
 Pinning status: pinned by tests/test_plan_oracle_pins.py (hand-priced cases, closed forms, monotonicity in
 the resources, exact recovery of known coefficients).  The paper prints no numeric example for either.
@@ -31,7 +31,7 @@ import numpy as np
 
 
 def iteration_time(lens: Sequence[int], coef: Sequence[float]) -> float:
-    """Sec. 5.6: alpha + beta * sum(len) + gamma * sum(len^2)."""
+    """Sec. 5.5, Eq. 7: alpha + beta * sum(len) + gamma * sum(len^2)."""
     a, b, g = coef
     return a + b * float(sum(lens)) + g * float(sum(int(x) * int(x) for x in lens))
 

@@ -1,7 +1,7 @@
-// Host-side planning helpers of the prefill path (no device code): the batching dynamic program of Sec. 5.4
+// Host-side planning helpers of the prefill path (no device code): the batching dynamic program of Sec. 5.3
 // (requests sorted by length, elastic instances sorted; f[i][k] = cheapest input latency of the first i requests
 // on the first k instances; interval sums from prefix arrays; last split points recorded for the backtrack) and the
-// least-squares fit of the iteration-time model of Sec. 5.6 (alpha + beta * sum(len) + gamma * sum(len^2)).
+// least-squares fit of the iteration-time model of Sec. 5.5 (alpha + beta * sum(len) + gamma * sum(len^2)).
 #include <math.h>
 
 #include <vector>

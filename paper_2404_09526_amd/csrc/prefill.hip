@@ -56,7 +56,8 @@ typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4_t;
 static int32_t prefill_q_tiles_bound(int32_t Tq, int32_t batch) { return Tq / kBM + batch; }
 
 // Global scratch memory of the prefill path: one 64-bit item counter (the first word of the block, the second is
-// spare) and the arrival counts of the start-of-round waits (one per XCD and KV head; room for one per query head).
+// spare) and the arrival counts of the start-of-round waits (one per round parity, XCD and KV head; room for one
+// per parity and query head).
 // Every launch
 // gets a tag of its own, so that a counter left by an earlier launch, or never written, is told from the current
 // one without clearing it first (a clearing kernel ahead of each launch costs about 6 us).  Tags start at a random
@@ -85,7 +86,7 @@ int32_t set_prefill_sync_ticks(int32_t ticks) {
 }
 size_t prefill_workspace_bytes(int32_t Tq, int32_t Tkv, int32_t batch, int32_t Hq, int32_t Hkv) {
     (void)Tq; (void)Tkv; (void)batch; (void)Hkv;
-    return ((size_t)8 * (2 + (size_t)(Hq > 0 ? Hq : 0)) + 255) / 256 * 256;   // pool and exit counters + one count per query head
+    return ((size_t)8 * (2 + 2 * (size_t)(Hq > 0 ? Hq : 0)) + 255) / 256 * 256;   // pool counter (+ a spare word) + two counts per query head
 }
 
 struct PrefillArgs {
@@ -853,28 +854,36 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
             // tiles it can hold per head.  Their items differ in length, so they would start the next round up to
             // that far apart, and since all run at the same speed the gap never closes: K/V then comes from memory
             // several times over.  So they wait for each other at the start of a dealt round: an arrival count per
-            // (XCD, KV head), tagged like the pool counter, and a wait that ends by itself: after 1/64 of the time
-            // this workgroup's previous item took (waiting pays only where the items are long and alike; where they
-            // differ a lot, as in a triangular sweep, it must cost next to nothing), at most after kSyncTicks.
+            // (round parity, XCD, KV head), tagged like the pool counter, and a wait that ends by itself: after 1/64
+            // of the time this workgroup's previous item took (waiting pays only where the items are long and alike;
+            // where they differ a lot, as in a triangular sweep, it must cost next to nothing), at most after
+            // kSyncTicks.  The deal goes back and forth, so a KV head is worked on by one set of workgroups in the
+            // even rounds and by another in the odd ones: with a count per parity, the same workgroups meet at
+            // a count every time, each adds one per round of that parity, and the round's target is that many full
+            // sets.  Every workgroup arrives at every waiting round whether its wait is cut short or not, so the
+            // total a count reaches is known beforehand, and the arrival that completes it clears the count (a
+            // launch replayed from a captured graph carries the tag it was recorded with and must not find its own
+            // earlier counts).
             if (a.group_sync && s >= 1 && (s + 1) * L <= M && tid == 0) {
                 const int m_next = s * L + ((s & 1) ? L - 1 - l : l);
-                unsigned long long* ctr = a.pool + 2 + x * width + (m_next % width) / G;
-                const uint32_t target = (uint32_t)(s * (L / width) * G);
+                unsigned long long* ctr = a.pool + 2 + ((s & 1) * 8 + x) * width + (m_next % width) / G;
+                const uint32_t set = (uint32_t)((L / width) * G);                       // workgroups on one KV head
+                const uint32_t target = set * (uint32_t)((s + (s & 1)) >> 1);            // rounds of this parity so far, this one included
+                const int s_last = M / L - 1;                                            // last round that waits
+                const uint32_t total = set * (uint32_t)((s & 1) ? (s_last + 1) >> 1 : s_last >> 1);
                 const int before_me = draw_finish(ctr, __hip_atomic_fetch_add(ctr, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-                if ((uint32_t)before_me + 1 < target) {
+                if ((uint32_t)before_me + 1 == total) {
+                    __hip_atomic_store(ctr, 0ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else if ((uint32_t)before_me + 1 < target) {
                     const long long t0 = wall_clock64();
                     const long long patience = min((long long)a.sync_ticks, (t0 - item_started) >> 6);
                     for (;;) {
                         const unsigned long long cur = __hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        // a count that is no longer this launch's was cleared by the last arrival (see below)
+                        // a count that is no longer this launch's was cleared by its last arrival (see above)
                         if ((uint32_t)(cur >> 32) != a.tag || (uint32_t)cur >= target) break;
                         if (wall_clock64() - t0 > patience) break;
                         __builtin_amdgcn_s_sleep(16);
                     }
-                } else if ((s + 2) * L > M) {
-                    // the last arrival of the last round that waits clears the count: a launch replayed from a
-                    // captured graph carries the tag it was recorded with and must not find its own earlier counts
-                    __hip_atomic_store(ctr, 0ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
             if (s > 0) wg_barrier();                                  // every wavefront is done with the LDS of the previous item
@@ -892,7 +901,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
                 qu = split ? i_pool & 7 : 0;                          // the queues take turns: still heaviest first
                 m = S * L + (split ? i_pool >> 3 : i_pool);
             }
-            if (m >= M) break;                                        // only when M <= L: fewer items than workgroups
+            if (m >= M) break;                                        // a last dealt round that is not full
             unsigned long long* claim = (s >= S - 1 && pool_items > 0) ? a.pool : nullptr;
             if (a.group_sync) item_started = wall_clock64();
             const bool ran = process(m / width, qu * width + m % width, claim);
@@ -930,11 +939,11 @@ esp_status launch_prefill(const void* q, const void* k, const void* v, const int
     a.tag = next_launch_tag();
     // start-of-round waits: one request with at least 512 KV tiles and a query chunk of at most an eighth of them
     // (a chunk against a long prefix: every query tile then sees nearly all of the shard, the items are alike), XCD
-    // split, the same number of workgroups on every KV head of an XCD; the counters ((XCD, KV head), at most
-    // 8 x heads_per_xcd) follow the pool counter
+    // split, the same number of workgroups on every KV head of an XCD; the counters ((round parity, XCD, KV head),
+    // at most 16 x heads_per_xcd) follow the pool counter
     a.group_sync = (a.heads_per_xcd > 0 && batch == 1 && Tkv >= 512 * kBN && (int64_t)Tkv >= 8 * (int64_t)Tq &&
                     (cus / 8) % a.heads_per_xcd == 0 &&
-                    8 * (2 + 8 * (size_t)a.heads_per_xcd) <= workspace_bytes) ? 1 : 0;
+                    8 * (2 + 16 * (size_t)a.heads_per_xcd) <= workspace_bytes) ? 1 : 0;
     a.sync_ticks = g_sync_ticks.load(std::memory_order_relaxed);
     hipLaunchKernelGGL(prefill_kernel, dim3(grid), dim3(kPfWaves * 64), 0, stream, a);
     return check_launch("prefill_kernel");

@@ -95,6 +95,43 @@ def test_chunk_against_a_long_prefix_with_round_start_waits(esp, cuda, ticks):
             esp.esp_debug_set_prefill_sync_ticks(was)
 
 
+def test_round_start_waits_replayed_from_a_graph(esp, cuda):
+    """The same shape recorded into a graph: replays carry the recorded launch's tag, so the arrival counts of the
+    round-start waits must have been cleared by the launch before (the arrival that completes a count clears it).
+    Replays alternate with eager calls on the same workspace; every result must equal the eager one bit for bit."""
+    pc = wl.contiguous_prefill("chunk-vs-prefix-graph", 4096, 32768 - 4096, [(0, 32768)], 32, 32, 34, cuda)
+    s = pc.shards[0]
+    ws = torch.zeros(esp.esp_prefill_workspace_bytes(pc.Tq, 32768, 1, 32, 32, 128), dtype=torch.uint8, device=cuda)
+    run = lambda O, L: esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos, softmax_scale=pc.scale, O=O, LSE=L, workspace=ws)
+    O_ref = torch.empty_like(pc.q); L_ref = torch.empty((pc.Tq, pc.Hq), dtype=torch.float32, device=cuda)
+    run(O_ref, L_ref)
+    torch.cuda.synchronize()
+    O_g, L_g = torch.empty_like(O_ref), torch.empty_like(L_ref)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(O_g, L_g)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run(O_g, L_g)
+    for rep in range(4):
+        say(f"graph replay {rep}")
+        O_g.copy_(torch.full_like(O_g, float("nan"))); L_g.copy_(torch.full_like(L_g, float("nan")))
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(O_g.view(torch.int16), O_ref.view(torch.int16)) and torch.equal(L_g.view(torch.int32), L_ref.view(torch.int32)), rep
+        if rep % 2 == 0:
+            O_e, L_e = torch.empty_like(O_ref), torch.empty_like(L_ref)
+            run(O_e, L_e)
+            torch.cuda.synchronize()
+            assert torch.equal(O_e.view(torch.int16), O_ref.view(torch.int16))
+    # the counts are clear again: nothing of this launch's tag is left behind the pool counter
+    words = ws.view(torch.int64)
+    assert int((words[2:2 + 2 * 32] != 0).sum()) == 0
+
+
 def test_config5_prefill_varlen_gqa(esp, cuda):
     pc = wl.config5_prefill(cuda)
     assert pc.visible_pairs_per_head == 2994661376

@@ -1,6 +1,6 @@
 """The host-side planning calls of libesp (no GPU needed) against oracle/plan.py: the dynamic program of
-Sec. 5.4 must find the cost the exhaustive enumeration finds, with a plan that is valid and prices to that cost;
-the fit of Sec. 5.6 must agree with the library least-squares routine."""
+Sec. 5.3 must find the cost the exhaustive enumeration finds, with a plan that is valid and prices to that cost;
+the fit of Sec. 5.5 must agree with the library least-squares routine."""
 import numpy as np
 import pytest
 

@@ -1,5 +1,5 @@
 """Pins of oracle/plan.py against things other than itself: hand-priced plans, closed forms, properties
-that any correct planner has, and exact recovery of known model coefficients (Sec. 5.4 and 5.6)."""
+that any correct planner has, and exact recovery of known model coefficients (Sec. 5.3 and 5.5)."""
 import math
 
 import numpy as np
@@ -9,7 +9,7 @@ from oracle import plan
 
 
 def test_iteration_time_is_the_three_term_model():
-    # Sec. 5.6 with numbers worked by hand: 2 + 0.5 * (3 + 4) + 0.25 * (9 + 16) = 11.75
+    # Sec. 5.5 (Eq. 7) with numbers worked by hand: 2 + 0.5 * (3 + 4) + 0.25 * (9 + 16) = 11.75
     assert plan.iteration_time([3, 4], (2.0, 0.5, 0.25)) == pytest.approx(11.75)
     assert plan.batch_cost([3, 4], (2.0, 0.5, 0.25)) == pytest.approx(11.75 / 3 + 11.75 / 4)
 

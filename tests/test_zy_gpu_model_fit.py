@@ -1,4 +1,4 @@
-"""Sec. 5.6 on this build's own measurements (a timing test: it runs after the parity tests)."""
+"""Sec. 5.5 (analytical model, Eq. 7) on this build's own measurements (a timing test: it runs after the parity tests)."""
 import numpy as np
 import pytest
 import torch
