@@ -55,7 +55,7 @@ extern "C" {
 typedef int32_t esp_status;
 #define ESP_OK                0
 #define ESP_ERR_INVALID_ARG  (-1) /* null pointer, negative size, Hq % Hkv != 0, P out of range */
-#define ESP_ERR_UNSUPPORTED  (-2) /* D != 128, or a head count the kernels do not cover        */
+#define ESP_ERR_UNSUPPORTED  (-2) /* D != 128                                                   */
 #define ESP_ERR_WORKSPACE    (-3) /* workspace missing or smaller than the matching *_bytes()  */
 #define ESP_ERR_HIP          (-4) /* a HIP launch failed; see esp_last_error()                 */
 
@@ -133,6 +133,10 @@ esp_status esp_partial_attn_prefill_f32(
  *   seq_offsets[B] = total_tokens; max_len >= every request's length.
  *   O [B,Hq,D] bf16, LSE [B,Hq] float.
  *   workspace: at least esp_decode_workspace_bytes(...) bytes, 256-byte aligned.
+ * Every Hq that is a multiple of Hkv is accepted (MHA, GQA, MQA).  With 4, 8, 16 or
+ * a multiple of 32 KV heads and 1, 2, 4 or 8 query heads per KV head a pool row is
+ * read in whole-row bursts; other head counts are read one KV head (256 bytes of a
+ * row) at a time.
  */
 esp_status esp_partial_attn_decode(
     const void* q, const void* k_pool, const void* v_pool, int64_t num_slots,

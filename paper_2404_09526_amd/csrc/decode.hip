@@ -57,8 +57,32 @@ struct DecodeGeom {
     int32_t ygroups;    // workgroups along y when a row has more than 8 head blocks
 };
 
-static DecodeGeom decode_geom(int32_t total_tokens, int32_t Hkv) {
+// Head counts of the row-burst kernel: whole 1 KiB head blocks (4 KV heads) that split the 8 wavefronts evenly,
+// and a query group that fits the registers.  Everything else goes to the per-head kernel below.
+static bool decode_burst_layout(int32_t Hq, int32_t Hkv) {
+    const int G = Hq / Hkv;
+    return (Hkv == 4 || Hkv == 8 || Hkv == 16 || Hkv % 32 == 0) && (G == 1 || G == 2 || G == 4 || G == 8);
+}
+// query heads of a KV head handled together by the per-head kernel: the largest of 8, 4, 2, 1 that divides the group
+static int decode_any_chunk(int G) { return G % 8 == 0 ? 8 : G % 4 == 0 ? 4 : G % 2 == 0 ? 2 : 1; }
+
+static DecodeGeom decode_geom(int32_t total_tokens, int32_t Hq, int32_t Hkv) {
     DecodeGeom g;
+    if (!decode_burst_layout(Hq, Hkv)) {
+        // per-head kernel: every wavefront of a workgroup works on the same KV head, 4 tokens per load and
+        // kDecTB loads per step, the 8 wavefronts on interleaved tokens
+        g.nhb_wg = 0;
+        g.nt = kDecWaves;
+        g.ygroups = Hkv;
+        int64_t step = (int64_t)kDecWaves * kDecTB * 4;
+        int64_t want = ((int64_t)total_tokens + kDecMaxWG - 1) / kDecMaxWG;
+        if (want < 4 * step) want = 4 * step;
+        want = (want + step - 1) / step * step;
+        g.range = (int32_t)want;
+        g.nwg = (int32_t)(((int64_t)total_tokens + want - 1) / want);
+        if (g.nwg < 1) g.nwg = 1;
+        return g;
+    }
     int nhb = Hkv / 4;
     g.nhb_wg = nhb < 8 ? nhb : 8;
     g.nt = kDecWaves / g.nhb_wg;
@@ -78,8 +102,7 @@ static DecodeGeom decode_geom(int32_t total_tokens, int32_t Hkv) {
 static size_t decode_slots(const DecodeGeom& g, int32_t B) { return (size_t)g.nwg + (size_t)B; }
 
 size_t decode_workspace_bytes(int32_t B, int32_t total_tokens, int32_t Hq, int32_t Hkv) {
-    if (Hkv % 4 != 0) return 0;
-    DecodeGeom g = decode_geom(total_tokens, Hkv);
+    DecodeGeom g = decode_geom(total_tokens, Hq, Hkv);
     size_t n = decode_slots(g, B) * (size_t)g.nt * (size_t)Hq;
     return n * (kHeadDim + 2) * sizeof(float) + 256;
 }
@@ -216,6 +239,146 @@ __global__ __launch_bounds__(kDecWaves * 64) void decode_partial_kernel(
     }
 }
 
+
+// The same partials for any head counts (MQA and GQA with 1, 2, 3, 5, ... KV heads, query groups of any size): one
+// workgroup per (token range, KV head, chunk of GC query heads of that KV head).  A pool row holds only 256 bytes of
+// one KV head, so a wavefront's load covers FOUR tokens (16 lanes x 16 bytes each), every 16-lane group keeps the
+// online-softmax state of its own tokens, and the four groups are combined when a request's segment ends.  Partial
+// slots as above, with the 8 wavefronts as the token interleave.  Less bandwidth per instruction than the row-burst
+// kernel (256-byte pieces instead of whole rows), which is why that one is kept for the shapes it covers.
+template <int GC>
+__global__ __launch_bounds__(kDecWaves * 64) void decode_partial_any_kernel(
+    const uint16_t* __restrict__ q, const uint4* __restrict__ k_pool, const uint4* __restrict__ v_pool,
+    const int32_t* __restrict__ slot_idx, const int32_t* __restrict__ seq_offsets, int32_t B, int32_t total_tokens,
+    int32_t range, int32_t Hq, int32_t Hkv, float scale_log2, float* __restrict__ part_acc,
+    float* __restrict__ part_ml) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int grp = lane >> 4;                                  // which of the load's four tokens
+    const int dseg = (lane & 15) * 8;
+    const int kvh = blockIdx.y;
+    const int G = Hq / Hkv;
+    const int h0 = kvh * G + blockIdx.z * GC;                   // first query head of this chunk
+    const int w = blockIdx.x;
+    const int64_t row_chunks = (int64_t)Hkv * (kHeadDim * 2 / 16);
+    const int lane_chunk = kvh * (kHeadDim * 2 / 16) + (lane & 15);
+
+    int32_t t0 = w * range;
+    const int32_t t1 = min(t0 + range, total_tokens);
+    if (t0 >= t1) return;
+    int lo = 0, hi = B;   // invariant: seq_offsets[lo] <= t0 < seq_offsets[hi]
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (seq_offsets[mid] <= t0) lo = mid; else hi = mid;
+    }
+    int b = lo;
+
+    while (t0 < t1) {
+        int32_t req_end = seq_offsets[b + 1];
+        if (req_end <= t0) { ++b; continue; }                   // empty request
+        const int32_t pe = min(t1, req_end);
+
+        float qf[GC][8];
+#pragma unroll
+        for (int gi = 0; gi < GC; ++gi) {
+            uint4 qw = *(const uint4*)(q + ((int64_t)b * Hq + h0 + gi) * kHeadDim + dseg);
+            unpack8(qw, qf[gi]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qf[gi][e] *= scale_log2;
+        }
+        float m[GC], l[GC], acc[GC][8];
+#pragma unroll
+        for (int gi = 0; gi < GC; ++gi) {
+            m[gi] = -INFINITY; l[gi] = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[gi][e] = 0.f;
+        }
+
+        // token of (step base, load u, wavefront, lane group) = base + 32 u + 4 wave + grp
+        for (int32_t base = t0; base < pe; base += kDecWaves * kDecTB * 4) {
+            uint4 kw[kDecTB], vw[kDecTB];
+            bool valid[kDecTB];
+#pragma unroll
+            for (int u = 0; u < kDecTB; ++u) {
+                const int32_t tok = base + u * (kDecWaves * 4) + wave * 4 + grp;
+                valid[u] = tok < pe;
+                const int32_t slot = slot_idx[valid[u] ? tok : t0];
+                const int64_t off = (int64_t)slot * row_chunks + lane_chunk;
+                kw[u] = k_pool[off];
+                vw[u] = v_pool[off];
+            }
+            float s[kDecTB][GC];
+#pragma unroll
+            for (int u = 0; u < kDecTB; ++u) {
+                float kf[8];
+                unpack8(kw[u], kf);
+#pragma unroll
+                for (int gi = 0; gi < GC; ++gi) {
+                    float d = 0.f;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) d = fmaf(qf[gi][e], kf[e], d);
+                    d = row16_sum(d);
+                    s[u][gi] = valid[u] ? d : -INFINITY;
+                }
+            }
+#pragma unroll
+            for (int gi = 0; gi < GC; ++gi) {
+                float mx = m[gi];
+#pragma unroll
+                for (int u = 0; u < kDecTB; ++u) mx = fmaxf(mx, s[u][gi]);
+                // a lane group may still be without any token: nothing to rescale, nothing to add
+                const float alpha = (mx == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m[gi] - mx);
+                m[gi] = mx;
+                l[gi] *= alpha;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[gi][e] *= alpha;
+#pragma unroll
+                for (int u = 0; u < kDecTB; ++u) s[u][gi] = valid[u] ? __builtin_amdgcn_exp2f(s[u][gi] - mx) : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < kDecTB; ++u) {
+                float vf[8];
+                unpack8(vw[u], vf);
+#pragma unroll
+                for (int gi = 0; gi < GC; ++gi) {
+                    l[gi] += s[u][gi];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[gi][e] = fmaf(s[u][gi], vf[e], acc[gi][e]);
+                }
+            }
+        }
+
+        // the four lane groups hold different tokens: combine them (butterfly over lane bits 4 and 5)
+#pragma unroll
+        for (int gi = 0; gi < GC; ++gi) {
+#pragma unroll
+            for (int sh = 16; sh <= 32; sh <<= 1) {
+                const float mo = __shfl_xor(m[gi], sh), lo2 = __shfl_xor(l[gi], sh);
+                const float mx = fmaxf(m[gi], mo);
+                const float ca = (mx == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m[gi] - mx);
+                const float cb = (mx == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mo - mx);
+                l[gi] = l[gi] * ca + lo2 * cb;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[gi][e] = acc[gi][e] * ca + __shfl_xor(acc[gi][e], sh) * cb;
+                m[gi] = mx;
+            }
+        }
+        if (grp == 0) {
+            const int64_t pslot = ((int64_t)(w + b) * kDecWaves + wave) * Hq;
+#pragma unroll
+            for (int gi = 0; gi < GC; ++gi) {
+                const int64_t ph = pslot + h0 + gi;
+                float4* dst = (float4*)(part_acc + ph * kHeadDim + dseg);
+                dst[0] = make_float4(acc[gi][0], acc[gi][1], acc[gi][2], acc[gi][3]);
+                dst[1] = make_float4(acc[gi][4], acc[gi][5], acc[gi][6], acc[gi][7]);
+                if (lane == 0) *(float2*)(part_ml + ph * 2) = make_float2(m[gi], l[gi]);
+            }
+        }
+        t0 = pe;
+        ++b;
+    }
+}
+
 // One workgroup per (request, head): 4 groups of 64 lanes split the partials, each lane owns
 // two output elements; the groups are then combined through LDS.
 __global__ __launch_bounds__(256) void decode_combine_kernel(const int32_t* __restrict__ seq_offsets,
@@ -286,12 +449,30 @@ esp_status launch_decode(const void* q, const void* k_pool, const void* v_pool, 
                          float softmax_scale, void* O, float* LSE, void* workspace, size_t workspace_bytes,
                          hipStream_t stream) {
     (void)workspace_bytes;
-    DecodeGeom g = decode_geom(total_tokens, Hkv);
+    DecodeGeom g = decode_geom(total_tokens, Hq, Hkv);
     size_t n = decode_slots(g, B) * (size_t)g.nt * (size_t)Hq;
     float* part_acc = (float*)workspace;
     float* part_ml = part_acc + n * kHeadDim;
     const int G = Hq / Hkv;
-    if (total_tokens > 0) {
+    if (total_tokens > 0 && g.nhb_wg == 0) {
+        const int GC = decode_any_chunk(G);
+        dim3 grid(g.nwg, Hkv, G / GC), block(kDecWaves * 64);
+        const float sl2 = softmax_scale * kLog2e;
+        if (Hkv > 65535 || G / GC > 65535) return fail(ESP_ERR_UNSUPPORTED, "decode: too many heads for one launch");
+#define ESP_DECODE_ANY(GG)                                                                                      \
+    hipLaunchKernelGGL(decode_partial_any_kernel<GG>, grid, block, 0, stream, (const uint16_t*)q,               \
+                       (const uint4*)k_pool, (const uint4*)v_pool, slot_idx, seq_offsets, B, total_tokens,      \
+                       g.range, Hq, Hkv, sl2, part_acc, part_ml)
+        switch (GC) {
+            case 1: ESP_DECODE_ANY(1); break;
+            case 2: ESP_DECODE_ANY(2); break;
+            case 4: ESP_DECODE_ANY(4); break;
+            default: ESP_DECODE_ANY(8); break;
+        }
+#undef ESP_DECODE_ANY
+        esp_status st = check_launch("decode_partial_any_kernel");
+        if (st != ESP_OK) return st;
+    } else if (total_tokens > 0) {
         dim3 grid(g.nwg, g.ygroups), block(kDecWaves * 64);
         float sl2 = softmax_scale * kLog2e;
 #define ESP_DECODE_LAUNCH(GG)                                                                                   \

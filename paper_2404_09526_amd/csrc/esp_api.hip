@@ -30,12 +30,9 @@ esp_status check_launch(const char* what) {
 }
 
 static bool heads_ok(int32_t Hq, int32_t Hkv) { return Hq > 0 && Hkv > 0 && Hq % Hkv == 0; }
-// head counts the decode kernel covers
-static bool decode_heads_supported(int32_t Hq, int32_t Hkv) {
-    if (!heads_ok(Hq, Hkv)) return false;
-    const int G = Hq / Hkv;
-    return (Hkv == 4 || Hkv == 8 || Hkv == 16 || Hkv % 32 == 0) && (G == 1 || G == 2 || G == 4 || G == 8);
-}
+// head counts the decode kernels cover: all (a row-burst kernel for 4, 8, 16 or a multiple of 32 KV heads with query
+// groups of 1, 2, 4 or 8; a per-head kernel for every other combination)
+static bool decode_heads_supported(int32_t Hq, int32_t Hkv) { return heads_ok(Hq, Hkv); }
 
 // ESP_DEBUG_VALIDATE=1 in the environment: the content of the device index arrays, trusted otherwise, is checked on
 // the host before the launch.  A debugging aid: it waits for the stream and copies the arrays back.
@@ -222,7 +219,7 @@ static esp_status decode_check(const void* q, const void* k_pool, const void* v_
         return fail(ESP_ERR_INVALID_ARG, "decode: null pool/slot_idx");
     if (!(softmax_scale == softmax_scale) || softmax_scale < 0.f) return fail(ESP_ERR_INVALID_ARG, "decode: bad softmax_scale");
     if (!decode_heads_supported(Hq, Hkv))
-        return fail(ESP_ERR_UNSUPPORTED, "decode: Hq=%d, Hkv=%d unsupported (Hkv 4, 8, 16 or a multiple of 32; Hq/Hkv 1, 2, 4 or 8)", Hq, Hkv);
+        return fail(ESP_ERR_UNSUPPORTED, "decode: Hq=%d, Hkv=%d unsupported", Hq, Hkv);
     return ESP_OK;
 }
 static esp_status decode_validate(const int32_t* slot_idx, const int32_t* seq_offsets, int32_t B, int32_t total_tokens, int32_t max_len,

@@ -41,7 +41,9 @@ def test_workspace_queries(lib):
     assert lib.esp_prefill_workspace_bytes(8192, 8192, 1, 32, 32, 64) == 0        # unsupported head_dim
     a = lib.esp_decode_workspace_bytes(64, 860000, 131072, 32, 32, 128)
     assert 0 < a < 64 << 20
-    assert lib.esp_decode_workspace_bytes(64, 860000, 131072, 32, 5, 128) == 0     # Hq % Hkv != 0
+    assert lib.esp_decode_workspace_bytes(64, 860000, 131072, 32, 5, 128) == 0     # Hq % Hkv != 0: the call is refused
+    for Hq, Hkv in [(32, 1), (8, 2), (12, 12), (24, 3), (40, 20)]:                # head counts of the per-head kernel
+        assert 0 < lib.esp_decode_workspace_bytes(64, 860000, 131072, Hq, Hkv, 128) < 512 << 20
 
 
 def test_host_side_argument_errors(lib):
@@ -70,8 +72,8 @@ def test_host_side_argument_errors(lib):
         == lib.ESP_ERR_WORKSPACE
     assert L.esp_partial_attn_decode(one, one, one, 8, one, one, 2, 10, 5, 4, 4, 128, f, one, one, one, 16, nul) \
         == lib.ESP_ERR_WORKSPACE
-    assert L.esp_partial_attn_decode(one, one, one, 8, one, one, 2, 10, 5, 12, 12, 128, f, one, one, one, 1 << 30, nul) \
-        == lib.ESP_ERR_UNSUPPORTED                                                         # Hkv = 12
+    assert L.esp_partial_attn_decode(one, one, one, 8, one, one, 2, 10, 5, 12, 12, 128, f, one, one, one, 16, nul) \
+        == lib.ESP_ERR_WORKSPACE                                                           # every head count is covered
     assert L.esp_partial_attn_decode(one, one, one, 8, one, one, 0, 0, 0, 4, 4, 128, f, one, one, nul, 0, nul) == lib.ESP_OK
     # decode on the built-in scratch block: the same checks, and sizes beyond the block are refused before any GPU call
     assert L.esp_partial_attn_decode_static(one, one, one, 8, one, one, 2, 10, 5, 6, 4, 128, f, one, one, nul) == lib.ESP_ERR_INVALID_ARG

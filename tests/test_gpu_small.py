@@ -156,6 +156,68 @@ def test_decode_in_two_master_groups(esp, cuda):
         run_decode_case(esp, sub)
 
 
+def test_multi_master_decode_on_two_streams(esp, cuda):
+    """Distributed decoding with several masters on one GPU (Sec. 4.2, Fig. 8): this instance is master of half of the
+    requests and only helps with the others.  The helped requests' queries arrive by a host-to-device copy (pinned
+    memory) on a second stream of default priority while the own requests are decoded; then the helped ones are decoded
+    and their (O, LSE) go back by device-to-host copies on the second stream while the own results are merged with the
+    peers' partials.  Several rounds in a row; both halves, what arrived on the host, and the merge against the oracle."""
+    lens = [300, 0, 1500, 64, 9, 2200, 700, 1]
+    dc = wl.decode_pool("multi-master", lens, 8192, 8, 4, 36, cuda, n_new=0)
+    h = dc.B // 2
+    off = wl.host_i32(dc.seq_offsets)
+    off_h = int(off[h])
+    own_off = dc.seq_offsets[:h + 1].contiguous(); peer_off = (dc.seq_offsets[h:] - off_h).contiguous()
+    own_slots, peer_slots = dc.slot_idx[:off_h].contiguous(), dc.slot_idx[off_h:].contiguous()
+    ml_own, ml_peer = int(dc.lens[:h].max()), int(dc.lens[h:].max())
+    q_host = dc.q[h:].cpu().pin_memory()                           # the other masters' queries, as they come off the wire
+    q_peer = torch.zeros_like(dc.q[h:])
+    O_own = torch.empty_like(dc.q[:h]); L_own = torch.empty((h, dc.Hq), dtype=torch.float32, device=cuda)
+    O_peer = torch.empty_like(dc.q[h:]); L_peer = torch.empty((dc.B - h, dc.Hq), dtype=torch.float32, device=cuda)
+    O_back = torch.empty(O_peer.shape, dtype=O_peer.dtype).pin_memory(); L_back = torch.empty(L_peer.shape, dtype=L_peer.dtype).pin_memory()
+    ws_own = torch.empty(esp.esp_decode_workspace_bytes(h, off_h, ml_own, dc.Hq, dc.Hkv, dc.D), dtype=torch.uint8, device=cuda)
+    ws_peer = torch.empty(esp.esp_decode_workspace_bytes(dc.B - h, dc.total_tokens - off_h, ml_peer, dc.Hq, dc.Hkv, dc.D),
+                          dtype=torch.uint8, device=cuda)
+    mO, mL = torch.empty_like(O_own), torch.empty_like(L_own)
+    wire = torch.cuda.Stream()                                      # default priority
+    main = torch.cuda.current_stream()
+    # the oracle's answers: its own pool image, every request, every head
+    kp = np.zeros((dc.num_slots, dc.Hkv, dc.D), np.uint16); vp = np.zeros_like(kp)
+    slots = wl.host_i32(dc.slot_idx)
+    for b, (kr, vr) in dc.host_rows.items():
+        oracle.kv_append(kr, vr, slots[off[b]:off[b + 1]], kp, vp)
+    Or, Lr = oracle.partial_attn_decode_all(wl.bits(dc.q), kp, vp, slots, off, dc.scale)
+    for rnd in range(3):
+        say(f"multi-master round {rnd}")
+        for t in (q_peer, O_own, O_peer, mO):
+            t.fill_(float("nan"))
+        O_back.fill_(float("nan")); L_back.fill_(float("nan"))
+        wire.wait_stream(main)
+        with torch.cuda.stream(wire):
+            q_peer.copy_(q_host, non_blocking=True)                 # peers' queries arrive while the own requests are decoded
+        esp.esp_partial_attn_decode(dc.q[:h], dc.k_pool, dc.v_pool, own_slots, own_off, ml_own, softmax_scale=dc.scale,
+                                    O=O_own, LSE=L_own, workspace=ws_own)
+        main.wait_stream(wire)
+        esp.esp_partial_attn_decode(q_peer, dc.k_pool, dc.v_pool, peer_slots, peer_off, ml_peer, softmax_scale=dc.scale,
+                                    O=O_peer, LSE=L_peer, workspace=ws_peer)
+        wire.wait_stream(main)
+        with torch.cuda.stream(wire):
+            O_back.copy_(O_peer, non_blocking=True); L_back.copy_(L_peer, non_blocking=True)   # results go back to their masters
+        esp.esp_merge_partials([O_own] + [p[:h] for p in dc.peer_O], [L_own] + [p[:h] for p in dc.peer_LSE], O=mO, LSE=mL)
+        main.wait_stream(wire)
+        torch.cuda.synchronize()
+        check_o_lse(O_own.float().cpu().numpy().reshape(-1, dc.D), L_own.cpu().numpy().reshape(-1), Or[:h].reshape(-1, dc.D),
+                    Lr[:h].reshape(-1), f"own requests, round {rnd}")
+        check_o_lse(O_back.float().numpy().reshape(-1, dc.D), L_back.numpy().reshape(-1), Or[h:].reshape(-1, dc.D),
+                    Lr[h:].reshape(-1), f"helped requests as received by their masters, round {rnd}")
+        assert torch.equal(O_back.view(torch.int16), O_peer.cpu().view(torch.int16)) and torch.equal(L_back.view(torch.int32), L_peer.cpu().view(torch.int32))
+        Op = np.stack([oracle.bf16_bits_to_f64(wl.bits(t)) for t in [O_own] + [p[:h].contiguous() for p in dc.peer_O]])
+        Lp = np.stack([t.cpu().numpy().astype(np.float64) for t in [L_own] + [p[:h] for p in dc.peer_LSE]])
+        Oref, Lref = oracle.merge_partials(Op, Lp)
+        check_o_lse(mO.float().cpu().numpy().reshape(-1, dc.D), mL.cpu().numpy().reshape(-1), Oref.reshape(-1, dc.D), Lref.reshape(-1),
+                    f"merge at the master, round {rnd}")
+
+
 # ------------------------------------------------------------------ prefill: layouts and edge cases
 @pytest.mark.parametrize("r_q", [0, 1, 2, 3])
 def test_striped_all_offsets(esp, cuda, r_q):
@@ -215,6 +277,29 @@ def test_decode_heads_and_empty_requests(esp, cuda, Hq, Hkv):
     esp.esp_kv_append(dc.new_k, dc.new_v, dc.new_slots, dc.k_pool, dc.v_pool)
     torch.cuda.synchronize()
     assert np.array_equal(wl.bits(dc.k_pool), kp) and np.array_equal(wl.bits(dc.v_pool), vp)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(32, 1), (4, 1), (8, 2), (12, 12), (24, 3), (40, 20), (5, 5), (48, 2)])
+def test_decode_any_head_counts(esp, cuda, Hq, Hkv):
+    """MQA, two KV heads, KV head counts that are no multiple of 4 and query groups other than 1, 2, 4, 8 (the
+    per-head kernel): empty requests, requests shorter than one load, requests across several token ranges."""
+    lens = [0, 1, 2, 3, 5, 0, 65, 700, 5000, 129, 0]
+    dc = wl.decode_pool(f"decode-any-{Hq}/{Hkv}", lens, 8192, Hq, Hkv, 34, cuda, n_new=0)
+    O, LSE, kp, vp = run_decode_case(esp, dc)
+    assert torch.isneginf(LSE[[0, 5, 10]]).all() and (O[[0, 5, 10]] == 0).all()
+
+
+def test_decode_mqa_many_ranges_and_merge(esp, cuda):
+    """MQA 32 / 1 at a size that is cut into many token ranges, then merged with peer partials."""
+    lens = wl.lognormal_lengths(16, 6000, 10, 60000, 35)
+    dc = wl.decode_pool("decode-mqa", lens, 1 << 18, 32, 1, 35, cuda, n_new=0)
+    O, LSE, _, _ = run_decode_case(esp, dc)
+    Om, Lm = esp.esp_merge_partials([O] + list(dc.peer_O), [LSE] + list(dc.peer_LSE))
+    torch.cuda.synchronize()
+    Op = np.stack([oracle.bf16_bits_to_f64(wl.bits(t)) for t in [O] + list(dc.peer_O)])
+    Lp = np.stack([t.cpu().numpy().astype(np.float64) for t in [LSE] + list(dc.peer_LSE)])
+    Oref, Lref = oracle.merge_partials(Op, Lp)
+    check_o_lse(Om.float().cpu().numpy().reshape(-1, 128), Lm.cpu().numpy().reshape(-1), Oref.reshape(-1, 128), Lref.reshape(-1), "MQA merge")
 
 
 def test_decode_many_ranges(esp, cuda):
