@@ -37,8 +37,9 @@ def parse():
                     help="skip the other full-size configurations that the default run times after its own steps "
                          "(configs[3] and configs[4]; a profiled run then holds launches of the headline shapes only)")
     ap.add_argument("--retain", action="store_true",
-                    help="proactive retention (scale-down during prefill): while each shard is attended, esp_kv_append keeps "
-                         "ALL its rows in a token pool from a second stream; reports the overhead against prefill alone")
+                    help="proactive retention (scale-down during prefill): every shard's rows are ALL kept in a token pool while the "
+                         "shard is attended, by esp_kv_append from a second stream and by esp_partial_attn_prefill_retain (from "
+                         "the tiles in on-chip memory); reports both overheads against prefill alone")
     ap.add_argument("--one-call", action="store_true",
                     help="also time one prefill call over all shards put together in order of position (not part of the default "
                          "run, so that the kernel statistics of a profiled default run hold launches of one shape only)")
@@ -335,21 +336,28 @@ def main():
             slots.append(perm[o:o + s.k.shape[0]].contiguous()); o += s.k.shape[0]
         side = torch.cuda.Stream()
 
-        def prefill_only(with_retain):
+        cu = lambda i: (None if single else pc.cu_q, None if single else pc.shards[i].cu_kv,
+                        None if single else pc.max_q, None if single else pc.shards[i].max_kv)
+
+        def prefill_only(mode):
             for i, s in enumerate(pc.shards):
-                if with_retain:
+                if mode == "side_stream":
                     side.wait_stream(torch.cuda.current_stream())
                     with torch.cuda.stream(side):
                         esp.esp_kv_append(s.k, s.v, slots[i], kp, vp)
-                esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos,
-                                             None if single else pc.cu_q, None if single else s.cu_kv,
-                                             None if single else pc.max_q, None if single else s.max_kv,
-                                             softmax_scale=pc.scale, causal=pc.causal, O=part_O[i], LSE=part_L[i], workspace=ws_pf)
-            if with_retain:
+                if mode == "fused":
+                    esp.esp_partial_attn_prefill_retain(pc.q, s.k, s.v, pc.q_pos, s.kv_pos, slots[i], kp, vp, *cu(i),
+                                                        softmax_scale=pc.scale, causal=pc.causal, O=part_O[i], LSE=part_L[i], workspace=ws_pf)
+                else:
+                    esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos, *cu(i),
+                                                 softmax_scale=pc.scale, causal=pc.causal, O=part_O[i], LSE=part_L[i], workspace=ws_pf)
+            if mode == "side_stream":
                 torch.cuda.current_stream().wait_stream(side)
 
-        times = {}
-        for mode in (False, True, False, True):
+        times, pool_ok = {}, {}
+        for mode in ("alone", "side_stream", "fused", "alone", "side_stream", "fused"):
+            if mode != "alone":
+                kp.zero_(); vp.zero_()
             prefill_only(mode); torch.cuda.synchronize()
             e0, e1 = ev(), ev()
             e0.record()
@@ -357,11 +365,13 @@ def main():
                 prefill_only(mode)
             e1.record(); torch.cuda.synchronize()
             times.setdefault(mode, []).append(e0.elapsed_time(e1) / args.steps)
-        t_plain, t_ret = min(times[False]), min(times[True])
-        ok = all(torch.equal(kp[slots[i].long()], s.k) and torch.equal(vp[slots[i].long()], s.v) for i, s in enumerate(pc.shards))
-        result["retain"] = {"ms_prefill_alone": t_plain, "ms_prefill_with_retention": t_ret,
-                            "overhead_pct": 100.0 * (t_ret / t_plain - 1.0), "rows_retained": n_rows,
-                            "bytes_moved": 2 * 2 * n_rows * pc.Hkv * pc.D * 2, "pool_matches": bool(ok)}
+            if mode != "alone":
+                pool_ok[mode] = all(torch.equal(kp[slots[i].long()], s.k) and torch.equal(vp[slots[i].long()], s.v) for i, s in enumerate(pc.shards))
+        t_plain, t_side, t_fused = min(times["alone"]), min(times["side_stream"]), min(times["fused"])
+        result["retain"] = {"ms_prefill_alone": t_plain, "ms_with_side_stream_scatter": t_side, "ms_fused": t_fused,
+                            "overhead_pct_side_stream": 100.0 * (t_side / t_plain - 1.0), "overhead_pct_fused": 100.0 * (t_fused / t_plain - 1.0),
+                            "rows_retained": n_rows, "bytes_written": 2 * n_rows * pc.Hkv * pc.D * 2,
+                            "pool_matches": {k: bool(v) for k, v in pool_ok.items()}}
     if args.one_call and single and len(pc.shards) > 1:
         # the same keys in one call: the shards concatenated and put in order of position (any order of rows is a
         # valid shard; ascending positions are what lets whole tiles be skipped or left unmasked)

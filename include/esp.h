@@ -210,6 +210,35 @@ esp_status esp_kv_append(
     void* stream);
 
 /*
+ * Prefill partial attention that keeps rows of the shard on the way (proactive
+ * scale-down, Sec. 4.1, Fig. 7: while the key-value segments circulate during
+ * prefill, every instance of the new, smaller group saves the rows the scaling
+ * plan assigns to it into its pool, so that no migration is needed afterwards;
+ * overhead claim of Sec. 7.4, Fig. 14).  The attention part is
+ * esp_partial_attn_prefill (out_f32 != 0: esp_partial_attn_prefill_f32, O then
+ * points to float); in the same pass
+ *   k_pool[retain_slot[t]] = k[t], v_pool[retain_slot[t]] = v[t]
+ * for every shard row t with retain_slot[t] >= 0, as esp_kv_append would do, but
+ * from the tiles that pass through on-chip memory anyway: the rows are read from
+ * device memory once.  Rows of requests that have no query row in this call, and
+ * rows no query can see, are kept all the same.  With Tq = 0 the call is a plain
+ * esp_kv_append.
+ *
+ *   retain_slot int32 [Tkv] (device); pools [num_slots,Hkv,D] bf16; slots that are
+ *   not negative must be distinct and below num_slots (checked only under
+ *   esp_debug_set_validate).  Everything else as in esp_partial_attn_prefill.
+ */
+esp_status esp_partial_attn_prefill_retain(
+    const void* q, const void* k, const void* v,
+    const int32_t* q_pos, const int32_t* kv_pos,
+    const int32_t* cu_q, const int32_t* cu_kv, int32_t batch,
+    int32_t Tq, int32_t Tkv, int32_t max_q, int32_t max_kv,
+    int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale, int32_t causal,
+    const int32_t* retain_slot, void* k_pool, void* v_pool, int64_t num_slots,
+    int32_t out_f32, void* O, float* LSE,
+    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Dense view of pool-resident rows: the inverse of esp_kv_append.  The key-value
  * rows a request keeps on this instance live in the token-granular pool at the
  * slots the scheduler chose (Sec. 4.1, Fig. 7; Sec. 6 "unified distributed

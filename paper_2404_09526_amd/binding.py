@@ -26,7 +26,7 @@ EXPORTS = (
     "esp_probe_mfma_bf16", "esp_probe_stream_read",
     "esp_partial_attn_prefill_f32", "esp_merge_partials_f32",
     "esp_debug_set_validate", "esp_debug_set_prefill_sync_ticks",
-    "esp_partial_attn_decode_static",
+    "esp_partial_attn_decode_static", "esp_partial_attn_prefill_retain",
 )
 ESP_DECODE_STATIC_SCRATCH_BYTES = 32 << 20
 
@@ -54,6 +54,8 @@ def _load() -> ctypes.CDLL:
     L.esp_debug_set_validate.restype = i32
     L.esp_debug_set_prefill_sync_ticks.argtypes = [i32]
     L.esp_debug_set_prefill_sync_ticks.restype = i32
+    L.esp_partial_attn_prefill_retain.argtypes = [vp] * 7 + [i32] * 8 + [f32, i32, vp, vp, vp, i64, i32, vp, vp, vp, sz, vp]
+    L.esp_partial_attn_prefill_retain.restype = i32
     L.esp_prefill_workspace_bytes.argtypes = [i32] * 6
     L.esp_prefill_workspace_bytes.restype = sz
     L.esp_partial_attn_decode.argtypes = [vp, vp, vp, i64, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, vp, vp, sz, vp]
@@ -183,6 +185,50 @@ def esp_partial_attn_prefill(q, k, v, q_pos, kv_pos, cu_q=None, cu_kv=None, max_
                                         batch, Tq, Tkv, int(max_q), int(max_kv), Hq, Hkv, D, float(softmax_scale),
                                         int(bool(causal)), _ptr(O), _ptr(LSE), _ptr(workspace), workspace.numel(),
                                         _stream()))
+    return O, LSE
+
+
+def esp_partial_attn_prefill_retain(q, k, v, q_pos, kv_pos, retain_slot, k_pool, v_pool, cu_q=None, cu_kv=None, max_q=None,
+                                    max_kv=None, softmax_scale=None, causal=True, O=None, LSE=None, workspace=None,
+                                    out_dtype=torch.bfloat16):
+    """esp_partial_attn_prefill that also keeps the shard rows t with retain_slot[t] >= 0 in the pool (in place),
+    from the tiles that pass through on-chip memory.  Returns (O, LSE); O bf16 or fp32 as in esp_partial_attn_prefill."""
+    _dev(q, torch.bfloat16, "q"); _dev(k, torch.bfloat16, "k"); _dev(v, torch.bfloat16, "v")
+    _dev(q_pos, torch.int32, "q_pos"); _dev(kv_pos, torch.int32, "kv_pos"); _dev(retain_slot, torch.int32, "retain_slot")
+    _dev(k_pool, torch.bfloat16, "k_pool"); _dev(v_pool, torch.bfloat16, "v_pool")
+    Tq, Hq, D = q.shape
+    Tkv, Hkv, Dk = k.shape
+    if (v.shape != k.shape or Dk != D or q_pos.shape != (Tq,) or kv_pos.shape != (Tkv,) or retain_slot.shape != (Tkv,)
+            or k_pool.shape != v_pool.shape or k_pool.shape[1:] != k.shape[1:]):
+        raise ValueError("prefill (retain): shape mismatch")
+    batch = 1
+    if cu_q is not None:
+        _dev(cu_q, torch.int32, "cu_q"); _dev(cu_kv, torch.int32, "cu_kv")
+        batch = cu_q.numel() - 1
+        if cu_kv.numel() != batch + 1:
+            raise ValueError("prefill (retain): cu_q and cu_kv differ in length")
+        if max_q is None or max_kv is None:
+            raise ValueError("prefill (retain): max_q and max_kv are required with cu_q/cu_kv")
+    else:
+        max_q, max_kv = Tq, Tkv
+    if softmax_scale is None:
+        softmax_scale = D ** -0.5
+    if O is None:
+        O = torch.empty(q.shape, dtype=out_dtype, device=q.device)
+    if LSE is None:
+        LSE = torch.empty((Tq, Hq), dtype=torch.float32, device=q.device)
+    if O.dtype not in (torch.bfloat16, torch.float32):
+        raise ValueError("prefill (retain): O must be bf16 or fp32")
+    _dev(O, O.dtype, "O"); _dev(LSE, torch.float32, "LSE")
+    if O.shape != q.shape or LSE.shape != (Tq, Hq):
+        raise ValueError("prefill (retain): output shape mismatch")
+    if workspace is None:
+        workspace = _workspace(esp_prefill_workspace_bytes(Tq, Tkv, batch, Hq, Hkv, D), q.device)
+    _check(lib.esp_partial_attn_prefill_retain(_ptr(q), _ptr(k), _ptr(v), _ptr(q_pos), _ptr(kv_pos), _ptr(cu_q), _ptr(cu_kv), batch,
+                                               Tq, Tkv, int(max_q), int(max_kv), Hq, Hkv, D, float(softmax_scale),
+                                               int(bool(causal)), _ptr(retain_slot), _ptr(k_pool), _ptr(v_pool), k_pool.shape[0],
+                                               1 if O.dtype == torch.float32 else 0, _ptr(O), _ptr(LSE), _ptr(workspace),
+                                               workspace.numel(), _stream()))
     return O, LSE
 
 

@@ -103,7 +103,9 @@ static esp_status prefill_entry(const void* q, const void* k, const void* v, con
                                 const int32_t* kv_pos, const int32_t* cu_q, const int32_t* cu_kv, int32_t batch,
                                 int32_t Tq, int32_t Tkv, int32_t max_q, int32_t max_kv, int32_t Hq, int32_t Hkv,
                                 int32_t D, float softmax_scale, int32_t causal, int32_t o_f32, void* O, float* LSE,
-                                void* workspace, size_t workspace_bytes, void* stream) {
+                                void* workspace, size_t workspace_bytes, void* stream,
+                                const int32_t* retain_slot = nullptr, void* k_pool = nullptr, void* v_pool = nullptr,
+                                int64_t num_slots = 0) {
     if (Tq < 0 || Tkv < 0 || batch < 1 || max_q < 0 || max_kv < 0)
         return fail(ESP_ERR_INVALID_ARG, "prefill: negative size or batch < 1");
     if (!heads_ok(Hq, Hkv)) return fail(ESP_ERR_INVALID_ARG, "prefill: Hq=%d must be a positive multiple of Hkv=%d", Hq, Hkv);
@@ -113,6 +115,15 @@ static esp_status prefill_entry(const void* q, const void* k, const void* v, con
     if (cu_q == nullptr && batch != 1) return fail(ESP_ERR_INVALID_ARG, "prefill: batch > 1 needs cu_q/cu_kv");
     if (cu_q == nullptr && (max_q != Tq || max_kv != Tkv))
         return fail(ESP_ERR_INVALID_ARG, "prefill: without cu_q/cu_kv, max_q/max_kv must equal Tq/Tkv");
+    if (retain_slot && Tkv > 0) {
+        if (!k || !v || !k_pool || !v_pool || num_slots <= 0) return fail(ESP_ERR_INVALID_ARG, "prefill (retain): null k/v/pool or empty pool");
+        if (debug_validate()) {
+            esp_status st = check_slots("prefill (retain)", retain_slot, Tkv, num_slots, true, true, (hipStream_t)stream);
+            if (st != ESP_OK) return st;
+        }
+        // no query row at all: nothing to attend, the rows are kept by the plain scatter
+        if (Tq == 0) return launch_kv_append(k, v, retain_slot, Tkv, k_pool, v_pool, Hkv * D * 2, (hipStream_t)stream);
+    }
     if (Tq == 0) return ESP_OK;
     if (!q || !O || !LSE || !q_pos) return fail(ESP_ERR_INVALID_ARG, "prefill: null q/q_pos/O/LSE");
     if (Tkv > 0 && (!k || !v || !kv_pos)) return fail(ESP_ERR_INVALID_ARG, "prefill: null k/v/kv_pos");
@@ -127,7 +138,20 @@ static esp_status prefill_entry(const void* q, const void* k, const void* v, con
         if (st != ESP_OK) return st;
     }
     return launch_prefill(q, k, v, q_pos, kv_pos, cu_q, cu_kv, batch, Tq, Tkv, max_q, max_kv, Hq, Hkv,
-                          softmax_scale, causal, o_f32, O, LSE, workspace, workspace_bytes, (hipStream_t)stream);
+                          softmax_scale, causal, o_f32, O, LSE, workspace, workspace_bytes,
+                          Tkv > 0 ? retain_slot : nullptr, k_pool, v_pool, (hipStream_t)stream);
+}
+
+esp_status esp_partial_attn_prefill_retain(const void* q, const void* k, const void* v, const int32_t* q_pos,
+                                           const int32_t* kv_pos, const int32_t* cu_q, const int32_t* cu_kv, int32_t batch,
+                                           int32_t Tq, int32_t Tkv, int32_t max_q, int32_t max_kv, int32_t Hq, int32_t Hkv,
+                                           int32_t D, float softmax_scale, int32_t causal, const int32_t* retain_slot,
+                                           void* k_pool, void* v_pool, int64_t num_slots, int32_t out_f32, void* O,
+                                           float* LSE, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!retain_slot && Tkv > 0) return fail(ESP_ERR_INVALID_ARG, "prefill (retain): null retain_slot");
+    if (num_slots < 0) return fail(ESP_ERR_INVALID_ARG, "prefill (retain): negative num_slots");
+    return prefill_entry(q, k, v, q_pos, kv_pos, cu_q, cu_kv, batch, Tq, Tkv, max_q, max_kv, Hq, Hkv, D, softmax_scale, causal,
+                         out_f32 ? 1 : 0, O, LSE, workspace, workspace_bytes, stream, retain_slot, k_pool, v_pool, num_slots);
 }
 
 esp_status esp_partial_attn_prefill(const void* q, const void* k, const void* v, const int32_t* q_pos,

@@ -92,6 +92,8 @@ size_t prefill_workspace_bytes(int32_t Tq, int32_t Tkv, int32_t batch, int32_t H
 struct PrefillArgs {
     const uint16_t* q; const uint16_t* k; const uint16_t* v;
     const int32_t* q_pos; const int32_t* kv_pos; const int32_t* cu_q; const int32_t* cu_kv;
+    const int32_t* retain_slot;       // [Tkv] pool slot of every shard row (negative: not kept), or null: nothing is kept
+    uint16_t* k_pool; uint16_t* v_pool;
     void* O; float* LSE;              // O: bf16 [Tq, Hq, 128], or fp32 of the same shape when o_f32 is set
     int32_t batch, Tq, Tkv, Hq, Hkv, causal, o_f32;
     int32_t q_tiles, heads_per_xcd;   // upper bound of the number of query tiles; query heads per XCD (0: no split)
@@ -127,6 +129,7 @@ constexpr int kStages = 4;            // LDS stages per operand; tile j lives in
 constexpr float kSumLimit = 1048576.f;  // 2^20: a tile's probability sum above this refreshes the offset
 
 #define ESP_GLOBAL __attribute__((address_space(1)))
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // One global -> LDS transfer of 64 x 16 bytes: lane L's 16 bytes (at gbase + voff) land at lds_addr + 16*L.
 // Issued as assembly so that the loads stay in flight across LDS reads of other stages; the matching
@@ -145,12 +148,29 @@ __device__ __forceinline__ void wg_barrier() { asm volatile("s_waitcnt lgkmcnt(0
 
 template <int V> struct IC { static constexpr int value = V; };
 
+// RETAIN: the variant that also keeps rows of the shard in the token pool while they pass through LDS (proactive
+// scale-down, Sec. 4.1 / Fig. 7).  Every KV tile of a request and KV head is OWNED by one item, which stores its K
+// and V rows to the pool slots that are not negative:
+//   * a request whose shard rows are about as many as its query rows (a striped shard, causal self-attention): the
+//     item of query tile i, first query head of the group, owns the four KV tiles 4i .. 4i+3 (the last query tile:
+//     all that remain).  Under a causal mask these are the tiles on its diagonal, the last ones of its sweep, which
+//     run the masked iteration anyway: the work is spread evenly over the items and costs each of them little;
+//   * any other request (a chunk against a long prefix): one item owns every tile, the last query tile's, or the
+//     first one's where the workgroups of a KV head walk the shard together (its turn comes in the last round).
+// An owner sweeps at least up to its last owned tile (tiles it cannot see pass through LDS without arithmetic), runs
+// the masked iteration from its first owned tile on, finds the slots in a ring of 8 LDS stages (the first four owned
+// tiles' slots are fetched at the start, the others with their K tiles), and stores the sweep's last four tiles, which
+// stay in LDS, after the sweep; an earlier tile j at the top of iteration j: complete in LDS by then, and issued
+// ahead of the iteration's transfers, so that the hand-counted waits still see those as the newest operations in
+// flight (they have to sit out the stores, though, which is why the tiles at the end are left for later).
+template <bool RETAIN>
 __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     // One LDS block, V stages first: an LDS instruction adds a 16-bit immediate to its address register, so with
     // each array's base folded into the per-lane register every operand read of the loop needs no address math.
     constexpr int kLdsV = 0, kLdsK = kLdsV + kStages * kTileBytes, kLdsPos = kLdsK + kStages * kKTileBytes,
                   kLdsQmm = kLdsPos + kStages * kBN * 4, kLdsSched = kLdsQmm + 2 * kPfWaves * 4,
-                  kLdsFlag = kLdsSched + kPfWaves * 64 * 8, kLdsTotal = kLdsFlag + 16;
+                  kLdsFlag = kLdsSched + kPfWaves * 64 * 8, kLdsSlot = kLdsFlag + 16,
+                  kLdsTotal = kLdsSlot + (RETAIN ? 8 * kBN * 4 : 0);
     __shared__ __attribute__((aligned(1024))) unsigned char smem[kLdsTotal];
     unsigned char (*lds_k)[kKTileBytes] = (unsigned char (*)[kKTileBytes])(smem + kLdsK);
     unsigned char (*lds_v)[kTileBytes] = (unsigned char (*)[kTileBytes])(smem + kLdsV);
@@ -185,18 +205,23 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     auto process = [&](const int rank, const int h, unsigned long long* claim_from) {
     const int kvh = h / G;
     int q_lo, q_hi, kv_lo, kv_hi;   // rows of this query tile; rows of its request in the shard
+    int own_lo = 0, own_hi = 0;     // KV tiles of the request whose rows this item keeps in the pool (none: equal)
     {
+        // query tiles of request r; a request without query rows whose shard rows may have to be kept gets one
+        // (empty) tile, so that it has a keeper
+        auto tiles_of = [&](int r) {
+            const int len = a.cu_q ? a.cu_q[r + 1] - a.cu_q[r] : a.Tq;
+            int nt = (len + kBM - 1) / kBM;
+            if (RETAIN && nt == 0 && a.retain_slot && a.cu_kv && a.cu_kv[r + 1] > a.cu_kv[r]) nt = 1;
+            return nt;
+        };
         int total = 0;
-        for (int r = 0; r < a.batch; ++r) {
-            int len = a.cu_q ? a.cu_q[r + 1] - a.cu_q[r] : a.Tq;
-            total += (len + kBM - 1) / kBM;
-        }
+        for (int r = 0; r < a.batch; ++r) total += tiles_of(r);
         if (rank >= total) return false;
         int tl = total - 1 - rank;   // later tiles of a causal request see more keys: run them first
-        int r = 0;
+        int r = 0, nt = 0;
         for (;; ++r) {
-            int len = a.cu_q ? a.cu_q[r + 1] - a.cu_q[r] : a.Tq;
-            int nt = (len + kBM - 1) / kBM;
+            nt = tiles_of(r);
             if (tl < nt) break;
             tl -= nt;
         }
@@ -205,10 +230,30 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         q_hi = min(q_lo + kBM, qe);
         kv_lo = a.cu_kv ? a.cu_kv[r] : 0;
         kv_hi = a.cu_kv ? a.cu_kv[r + 1] : a.Tkv;
+        if (RETAIN && a.retain_slot != nullptr && h % G == 0) {   // which KV tiles this item owns (see the kernel's head)
+            const int tiles = (kv_hi - kv_lo + kBN - 1) / kBN, per = kBM / kBN;
+            if (!a.group_sync && a.causal && tiles <= per * nt + per) {
+                own_lo = min(per * tl, tiles);
+                own_hi = tl == nt - 1 ? tiles : min(per * tl + per, tiles);
+            } else if (tl == (a.group_sync ? 0 : nt - 1)) {
+                own_hi = tiles;
+            }
+        }
     }
+    // the same for every lane by construction; said explicitly, since base addresses of the tile transfers derive
+    // from them and must sit in scalar registers
+    q_lo = __builtin_amdgcn_readfirstlane(q_lo); q_hi = __builtin_amdgcn_readfirstlane(q_hi);
+    kv_lo = __builtin_amdgcn_readfirstlane(kv_lo); kv_hi = __builtin_amdgcn_readfirstlane(kv_hi);
+    own_lo = __builtin_amdgcn_readfirstlane(own_lo); own_hi = __builtin_amdgcn_readfirstlane(own_hi);
+    // The rest of the item exists twice in the keeping kernel: as everywhere else, and with an owner's extras.
+    // (One body with the extras behind a run-time flag costs the items that own nothing dearly: measured +25 % on
+    // a GQA batch, where three items in four own nothing, against +1.6 % with two bodies.)
+    auto body = [&](auto keep_c) {
+    constexpr bool KEEP = RETAIN && decltype(keep_c)::value != 0;
     const int kv_len = kv_hi - kv_lo;
     const int nkt = (kv_len + kBN - 1) / kBN;
     const int tail_rows = kv_len - (nkt - 1) * kBN;    // rows of the last tile (64 when not ragged)
+    const int ragged_tile = tail_rows < kBN ? nkt - 1 : -8;          // index of the ragged last tile, if any
 
     // ---- global -> LDS in transfers of 64 lanes x 16 bytes = 1 KiB of consecutive LDS bytes.
     //      V tile (rows of 256 B, chunks XOR-swizzled): wavefront w moves rows 8w .. 8w+7 in two transfers; lane L
@@ -270,23 +315,71 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // written before the barrier that follows
     };
 
+    // an owner's extras: slots of an owned tile t into stage t % 8 of the slot ring (wavefront 6), and the stores of
+    // owned tiles' K and V rows from LDS to the pool (wavefront w: rows 8w .. 8w+7)
+    const int32_t* sreq = KEEP ? a.retain_slot + kv_lo : nullptr;
+    auto fetch_slots = [&](int t) {
+        if (!KEEP || wave != 6 || t < own_lo || t >= own_hi) return;
+        const int rows = min(kBN, kv_len - t * kBN);
+        load_to_lds_b32(lds_base + kLdsSlot + (t & 7) * (kBN * 4), sreq + t * kBN, min(lane, rows - 1) * 4);
+    };
+    // Slots past the end of a ragged last tile become -1 (wavefront 6, once the tile's slots have landed and a
+    // barrier before anyone reads them), so that the stores test the slot alone.
+    auto seal_slots = [&]() {
+        if (!KEEP || wave != 6 || ragged_tile < own_lo || ragged_tile >= own_hi) return;
+        if (lane >= tail_rows) ((int32_t*)(smem + kLdsSlot))[(ragged_tile & 7) * kBN + lane] = -1;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    };
+    // K and V rows of tile t (both in stage st) to the pool, at the top of iteration t.  Every wavefront stores
+    // exactly the LDS bytes its own transfers fill: of V the rows 8w .. 8w+7, of K the 1 KiB pieces w and w + 8 of
+    // the padded tile (wavefront 7 also the 17th), lane L the 16 bytes at 1024 n + 16 L, i.e. row B / 272 at
+    // B % 272 (nothing if that is padding).  The K stage is refilled during this very iteration, but each
+    // wavefront's own refills follow its own reads in program order, and it reads nobody else's bytes.
+    // All LDS reads first (slots and rows, one round trip), then the stores.
+    auto keep_tile = [&](int t, int st) {
+        if (!KEEP) return;
+        if (t < own_lo || t >= own_hi) return;
+        const int32_t* ring = (const int32_t*)(smem + kLdsSlot) + (t & 7) * kBN;
+        const unsigned char* kt = smem + kLdsK + st * kKTileBytes;
+        const unsigned char* vt = smem + kLdsV + st * kTileBytes;
+        const int r0 = wave * 8 + st_sub, r1 = r0 + 4;
+        const int b0 = 1024 * wave + 16 * lane, b1 = b0 + 8192, b2 = 16384 + 16 * lane;
+        const int kr0 = b0 / kKRow, kr1 = b1 / kKRow, kr2 = b2 / kKRow;
+        const int kw0 = b0 - kr0 * kKRow, kw1 = b1 - kr1 * kKRow, kw2 = b2 - kr2 * kKRow;
+        const int32_t sv0 = ring[r0], sv1 = ring[r1];
+        const int32_t sk0 = ring[kr0], sk1 = ring[kr1], sk2 = ring[kr2];
+        const uint4 wv0 = *(const uint4*)(vt + r0 * 256 + ((st_p ^ ((r0 & 3) << 2)) << 4));
+        const uint4 wv1 = *(const uint4*)(vt + r1 * 256 + ((st_p ^ ((r1 & 3) << 2)) << 4));
+        const uint4 wk0 = *(const uint4*)(kt + b0), wk1 = *(const uint4*)(kt + b1), wk2 = *(const uint4*)(kt + b2);
+        // address of a pool row's piece: one 32 x 32 -> 64-bit multiply-add each
+        const uint32_t row_pitch = (uint32_t)a.Hkv * (kHeadDim * 2);
+        ESP_GLOBAL char* kb = (ESP_GLOBAL char*)a.k_pool + (uint32_t)kvh * (kHeadDim * 2);
+        ESP_GLOBAL char* vb = (ESP_GLOBAL char*)a.v_pool + (uint32_t)kvh * (kHeadDim * 2) + 16 * st_p;
+        if (sk0 >= 0 && kw0 < 256) *(ESP_GLOBAL u32x4*)(kb + (uint64_t)(uint32_t)sk0 * row_pitch + kw0) = u32x4{wk0.x, wk0.y, wk0.z, wk0.w};
+        if (sk1 >= 0 && kw1 < 256) *(ESP_GLOBAL u32x4*)(kb + (uint64_t)(uint32_t)sk1 * row_pitch + kw1) = u32x4{wk1.x, wk1.y, wk1.z, wk1.w};
+        if (wave == 7 && sk2 >= 0 && kw2 < 256) *(ESP_GLOBAL u32x4*)(kb + (uint64_t)(uint32_t)sk2 * row_pitch + kw2) = u32x4{wk2.x, wk2.y, wk2.z, wk2.w};
+        if (sv0 >= 0) *(ESP_GLOBAL u32x4*)(vb + (uint64_t)(uint32_t)sv0 * row_pitch) = u32x4{wv0.x, wv0.y, wv0.z, wv0.w};
+        if (sv1 >= 0) *(ESP_GLOBAL u32x4*)(vb + (uint64_t)(uint32_t)sv1 * row_pitch) = u32x4{wv1.x, wv1.y, wv1.z, wv1.w};
+    };
+
     // ---- this lane's query row (column of S^T); its position is needed first (schedule scan), so it is loaded first
     const int qi = lane & 31, hi = lane >> 5;
     const int my_row = q_lo + wave * 32 + qi;
     const bool row_ok = my_row < q_hi;
-    const int ld_row = row_ok ? my_row : q_hi - 1;
+    const int ld_row = row_ok ? my_row : max(q_hi - 1, 0);            // (an empty tile of the keeping variant: any row)
     // effective query position: non-causal rows see every real key
     const int my_qpos = a.causal ? a.q_pos[ld_row] : INT_MAX - 1;   // INT_MAX marks rows past a ragged tail
 
     // the first tiles are requested right away, so that their latency hides behind the Q load and the schedule
     // scan (tiles the scan later finds hidden are fetched for nothing, which is harmless: they exist)
-    const int ragged_tile = tail_rows < kBN ? nkt - 1 : -8;          // index of the ragged last tile, if any
     if (nkt > 4) {                                                   // the usual case, without a conditional in it
         fetch_k(kreq, 0, false); fetch_v(vreq, preq, 0, false);
         fetch_k(kreq + tile_bytes, 1, false); fetch_v(vreq + tile_bytes, preq + kBN, 1, false);
         fetch_k(kreq + 2 * tile_bytes, 2, false);
         fetch_k(kreq + 3 * tile_bytes, 3, false);
+        fetch_slots(own_lo); fetch_slots(own_lo + 1); fetch_slots(own_lo + 2); fetch_slots(own_lo + 3);
     } else {
+        fetch_slots(own_lo); fetch_slots(own_lo + 1); fetch_slots(own_lo + 2); fetch_slots(own_lo + 3);
         if (nkt > 0) { fetch_k(kreq, 0, 0 == ragged_tile); fetch_v(vreq, preq, 0, 0 == ragged_tile); }
         if (nkt > 1) { fetch_k(kreq + tile_bytes, 1, 1 == ragged_tile); fetch_v(vreq + tile_bytes, preq + kBN, 1, 1 == ragged_tile); }
         if (nkt > 2) fetch_k(kreq + 2 * tile_bytes, 2, 2 == ragged_tile);
@@ -387,6 +480,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         n_vis = last_vis + 1;
         first_mask = fm;
         n_need = lw + 1;
+        if (KEEP) n_vis = max(n_vis, own_hi);                       // every owned tile passes through LDS, seen or not
     }
 
     // ---- operand read offsets
@@ -560,6 +654,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         constexpr int ST1 = (ST + 1) % kStages, ST2 = (ST + 2) % kStages, ST3 = (ST + 3) % kStages;
         floatx16 (&sc)[2] = sbuf[PAR];
         floatx16 (&sn)[2] = sbuf[PAR ^ 1];
+        if (KEEP && !PLAIN && j < n_vis - 4) keep_tile(j, ST);
         if (!PLAIN && j >= mask_from) apply_mask(sc, ST);
         const bool do_k = PLAIN || j < n_vis - 4, do_v = PLAIN || j < n_vis - 2;
         const bool tail_k = !PLAIN && j + 4 == ragged_tile, tail_v = !PLAIN && j + 2 == ragged_tile;
@@ -587,7 +682,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
             // pipeline); the odd ones of wavefronts 7 and 0 go first, so that "all but the last four have landed"
             // is the same wait for every wavefront
             if (m == 1) {
-                if (do_k) fetch_k_part(k_next, ST, tail_k, 2);
+                if (do_k) { if (!PLAIN && j >= own_lo) fetch_slots(j + 4); fetch_k_part(k_next, ST, tail_k, 2); }
                 if (do_v) fetch_v_part(v_next, p_next, ST2, tail_v, 2);
             }
             if (do_k && (m == 3 || m == 6)) fetch_k_part(k_next, ST, tail_k, m / 6);
@@ -600,7 +695,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         if (do_k) wait_vm<4>();
         else if (do_v) wait_vm<2>();
         else wait_vm<0>();
-        if (__builtin_expect(j + 1 == ragged_tile, 0)) seal_tail(ST1);   // its positions landed with V(j+1)
+        if (__builtin_expect(j + 1 == ragged_tile, 0)) { seal_tail(ST1); seal_slots(); }   // its positions landed with V(j+1), its slots before
         asm volatile("s_barrier" :: "v"(sn[0]), "v"(sn[1]), "v"(oacc[0]), "v"(oacc[1]), "v"(oacc[2]), "v"(oacc[3]),
                                     "v"(pf[1][1].v) : "memory");
     };
@@ -611,6 +706,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     // in flight understands, or every later reuse of these registers makes it wait for "pending" loads
     asm volatile("" :: "v"(qf[0]), "v"(qf[1]), "v"(qf[2]), "v"(qf[3]), "v"(qf[4]), "v"(qf[5]), "v"(qf[6]), "v"(qf[7]));
     if (ragged_tile >= 0 && ragged_tile < 2) seal_tail(ragged_tile);
+    if (ragged_tile >= 0 && ragged_tile < 2) seal_slots();          // (in every other case before the iteration ahead of its own)
     wg_barrier();
     if (n_need > 0) {
         read_k(0, 0, 0);
@@ -640,7 +736,10 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     //      stream has no conditional code at all (a wavefront may leave this part earlier than its neighbours:
     //      the barriers and transfers per iteration are the same in both kinds);
     //   2. general iterations for the rest, again in groups of four, then one by one.
-    const int n_plain = max(0, min(min(min(n_vis - 4, n_need), mask_from), ragged_tile >= 0 ? nkt - 5 : INT_MAX)) & ~3;
+    //      (an owner: also short of its first owned tile, unless that is one of the sweep's last four, which are
+    //      stored after the sweep)
+    const int n_plain = max(0, min(min(min(min(n_vis - 4, n_need), mask_from), ragged_tile >= 0 ? nkt - 5 : INT_MAX),
+                                   KEEP && own_lo < n_vis - 4 ? own_lo : INT_MAX)) & ~3;
     int j = 0;
     for (; j < n_plain; j += 4) {
         iteration(IC<0>{}, IC<0>{}, IC<1>{}, j);
@@ -674,6 +773,8 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     for (int jj = n_need; jj < n_vis; ++jj) {
         const bool do_k = jj < n_vis - 4, do_v = jj < n_vis - 2;
         const bool tail_k = jj + 4 == ragged_tile, tail_v = jj + 2 == ragged_tile;
+        if (KEEP && jj < n_vis - 4) keep_tile(jj, jj & 3);
+        if (do_k && jj >= own_lo) fetch_slots(jj + 4);
         if (do_k) fetch_k_part(k_next, jj & 3, tail_k, 2);
         if (do_v) fetch_v_part(v_next, p_next, (jj + 2) & 3, tail_v, 2);
         if (do_k) { fetch_k_part(k_next, jj & 3, tail_k, 0); fetch_k_part(k_next, jj & 3, tail_k, 1); }
@@ -682,8 +783,15 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         if (do_k) wait_vm<4>();
         else if (do_v) wait_vm<2>();
         else wait_vm<0>();
-        if (__builtin_expect(jj + 1 == ragged_tile, 0)) seal_tail((jj + 1) & 3);
+        if (__builtin_expect(jj + 1 == ragged_tile, 0)) { seal_tail((jj + 1) & 3); seal_slots(); }
         asm volatile("s_barrier" ::: "memory");
+    }
+
+    // The last four tiles of the sweep are still in their stages, with nothing in flight any more: an owner stores
+    // those it owns now (under a causal mask the tiles on its diagonal, i.e. all it owns), where no hand-counted
+    // wait has to sit out the stores.
+    if (KEEP) {
+        for (int t = max(max(own_lo, n_vis - 4), 0); t < own_hi; ++t) keep_tile(t, t & 3);
     }
 
     // ---- the plain sweep, for a workgroup whose optimistic pass met scores outside its range: one tile at a
@@ -824,6 +932,11 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     if (claim_from && tid == 0) *lds_next = draw_finish(claim_from, next_item);
     return true;
     };
+    if constexpr (RETAIN) {
+        if (own_hi > own_lo) return body(IC<1>{});
+    }
+    return body(IC<0>{});
+    };
 
     // ---- persistent workgroups, one per CU.  Consecutive workgroup ids land on consecutive XCDs, each with a
     //      private L2, so XCD x keeps the heads [x * per, (x + 1) * per) (all query heads of a KV head together):
@@ -919,12 +1032,13 @@ esp_status launch_prefill(const void* q, const void* k, const void* v, const int
                           const int32_t* cu_q, const int32_t* cu_kv, int32_t batch, int32_t Tq, int32_t Tkv,
                           int32_t max_q, int32_t max_kv, int32_t Hq, int32_t Hkv, float softmax_scale,
                           int32_t causal, int32_t o_f32, void* O, float* LSE, void* workspace, size_t workspace_bytes,
-                          hipStream_t stream) {
+                          const int32_t* retain_slot, void* k_pool, void* v_pool, hipStream_t stream) {
     (void)max_q; (void)max_kv;
     PrefillArgs a;
     a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
     a.q_pos = q_pos; a.kv_pos = kv_pos; a.cu_q = cu_q; a.cu_kv = cu_kv;
     a.O = O; a.LSE = LSE; a.o_f32 = o_f32 ? 1 : 0;
+    a.retain_slot = retain_slot; a.k_pool = (uint16_t*)k_pool; a.v_pool = (uint16_t*)v_pool;
     a.batch = batch; a.Tq = Tq; a.Tkv = Tkv; a.Hq = Hq; a.Hkv = Hkv; a.causal = causal ? 1 : 0;
     a.scale_log2 = softmax_scale * kLog2e;
     a.q_tiles = prefill_q_tiles_bound(Tq, batch);
@@ -945,7 +1059,10 @@ esp_status launch_prefill(const void* q, const void* k, const void* v, const int
                     (cus / 8) % a.heads_per_xcd == 0 &&
                     8 * (2 + 16 * (size_t)a.heads_per_xcd) <= workspace_bytes) ? 1 : 0;
     a.sync_ticks = g_sync_ticks.load(std::memory_order_relaxed);
-    hipLaunchKernelGGL(prefill_kernel, dim3(grid), dim3(kPfWaves * 64), 0, stream, a);
+    if (retain_slot)
+        hipLaunchKernelGGL(prefill_kernel<true>, dim3(grid), dim3(kPfWaves * 64), 0, stream, a);
+    else
+        hipLaunchKernelGGL(prefill_kernel<false>, dim3(grid), dim3(kPfWaves * 64), 0, stream, a);
     return check_launch("prefill_kernel");
 }
 

@@ -75,6 +75,35 @@ def test_config2_prefill_striped_4_shards(esp, cuda):
     check_prefill_sampled(esp, pc, *wl.PARITY_SAMPLES[pc.name])
 
 
+def test_config2_prefill_with_retention(esp, cuda):
+    """Config 2's shards 0 and 3 through esp_partial_attn_prefill_retain, every row kept at a random slot of a pool with
+    room for twice as many: the pool rows against the oracle's scatter (every kept row, bit for bit, plus the sum of
+    all 16-bit patterns of the pool: nothing else was touched), O and LSE against the oracle on the parity samples."""
+    pc = wl.config2_prefill(cuda)
+    rows, heads, reqs = wl.prefill_parity_samples(pc, *wl.PARITY_SAMPLES[pc.name])
+    ri, hi = torch.from_numpy(rows).to(cuda), torch.from_numpy(heads).to(cuda)
+    rng = np.random.default_rng(5)
+    S = 2 * 8192
+    for si in (0, 3):
+        s = pc.shards[si]
+        slots = rng.permutation(S)[:8192].astype(np.int32)
+        slots[rng.random(8192) > 0.9] = -1
+        kp = torch.zeros((S, pc.Hkv, pc.D), dtype=torch.bfloat16, device=cuda); vp = torch.zeros_like(kp)
+        O = torch.full(pc.q.shape, float("nan"), dtype=torch.float32, device=cuda)
+        LSE = torch.full((pc.Tq, pc.Hq), float("nan"), dtype=torch.float32, device=cuda)
+        say(f"{pc.name} shard {si} with retention: kept {int((slots >= 0).sum())} of 8192 rows, pool {S} slots")
+        esp.esp_partial_attn_prefill_retain(pc.q, s.k, s.v, pc.q_pos, s.kv_pos, torch.from_numpy(slots).to(cuda), kp, vp,
+                                            softmax_scale=pc.scale, causal=True, O=O, LSE=LSE)
+        torch.cuda.synchronize()
+        kh = np.zeros((S, pc.Hkv, pc.D), np.uint16); vh = np.zeros_like(kh)
+        oracle.kv_append(wl.bits(s.k), wl.bits(s.v), slots, kh, vh)
+        assert np.array_equal(wl.bits(kp), kh) and np.array_equal(wl.bits(vp), vh)
+        Or, Lr = oracle.partial_attn(wl.bits(pc.q), wl.bits(s.k), wl.bits(s.v), wl.host_i32(pc.q_pos), wl.host_i32(s.kv_pos), pc.scale,
+                                     True, rows, heads)
+        check_o_lse(O[ri, hi].cpu().numpy(), LSE[ri, hi].cpu().numpy(), Or, Lr, f"{pc.name} shard {si} (retain)")
+        assert not torch.isnan(O).any() and not torch.isnan(LSE).any()
+
+
 def test_config4_prefill_long_context(esp, cuda):
     pc = wl.config4_prefill(cuda)
     assert pc.visible_pairs_per_head == 32768 * 262144

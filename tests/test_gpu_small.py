@@ -686,3 +686,99 @@ def test_prefill_randomized_layouts(esp, cuda, seed):
         pc.causal = False
     say(f"layout: chunks={chunks} shards={n_shards} mode={mode}")
     run_prefill_case(esp, pc)
+
+
+# ------------------------------------------------------------------ prefill that keeps rows of the shard on the way
+def run_retain_case(esp, pc, seed, keep_fraction=0.7, out_dtype=torch.bfloat16):
+    """Every shard through esp_partial_attn_prefill_retain with seeded slots (distinct; some rows not kept) into a pool
+    full of noise: O and LSE must match the oracle (and agree with esp_partial_attn_prefill); the pool
+    must be, bit for bit, what the oracle's scatter makes of the same noise."""
+    rng = np.random.default_rng(seed)
+    qb, qp = wl.bits(pc.q), wl.host_i32(pc.q_pos)
+    cu_q = wl.host_i32(pc.cu_q)
+    Tq, Hq, D = pc.q.shape
+    rows = np.repeat(np.arange(Tq, dtype=np.int64), Hq); heads = np.tile(np.arange(Hq, dtype=np.int64), Tq)
+    req_of_row = np.searchsorted(cu_q, np.arange(Tq), side="right") - 1
+    single = pc.batch == 1
+    to = lambda a: torch.from_numpy(a.view(np.int16)).to(pc.q.device).view(torch.bfloat16)
+    for si, s in enumerate(pc.shards):
+        Tkv = s.k.shape[0]
+        S = max(64, 2 * Tkv + 17)
+        kp = (rng.integers(0, 65536, (S, pc.Hkv, D)).astype(np.uint16)) & 0x3FFF
+        vp = (rng.integers(0, 65536, (S, pc.Hkv, D)).astype(np.uint16)) & 0x3FFF
+        slots = rng.permutation(S)[:Tkv].astype(np.int32)
+        slots[rng.random(Tkv) > keep_fraction] = -1
+        say(f"{pc.name} shard {si} with retention: Tq={Tq} Tkv={Tkv} Hq={Hq} Hkv={pc.Hkv} batch={pc.batch} kept={int((slots >= 0).sum())} pool={S}")
+        kp_d, vp_d = to(kp), to(vp)
+        O = torch.full(pc.q.shape, float("nan"), dtype=out_dtype, device=pc.q.device)
+        LSE = torch.full((Tq, Hq), float("nan"), dtype=torch.float32, device=pc.q.device)
+        args = (None if single else pc.cu_q, None if single else s.cu_kv, None if single else pc.max_q, None if single else s.max_kv)
+        esp.esp_partial_attn_prefill_retain(pc.q, s.k, s.v, pc.q_pos, s.kv_pos, torch.from_numpy(slots).to(pc.q.device), kp_d, vp_d, *args,
+                                            softmax_scale=pc.scale, causal=pc.causal, O=O, LSE=LSE)
+        torch.cuda.synchronize()
+        oracle.kv_append(wl.bits(s.k), wl.bits(s.v), slots, kp, vp)
+        assert np.array_equal(wl.bits(kp_d), kp), f"{pc.name} shard {si}: K pool differs"
+        assert np.array_equal(wl.bits(vp_d), vp), f"{pc.name} shard {si}: V pool differs"
+        if Tq == 0:
+            continue
+        O0, L0 = esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos, *args, softmax_scale=pc.scale, causal=pc.causal,
+                                              out_dtype=out_dtype)
+        torch.cuda.synchronize()
+        # against the call that keeps nothing: the same log-sum-exp bit for bit; O may differ in the last bits (an item
+        # that keeps rows runs the masked iteration on more tiles, and that one normalises by the rounded probabilities)
+        assert torch.equal(LSE.view(torch.int32), L0.view(torch.int32))
+        assert torch.allclose(O.float(), O0.float(), rtol=2.0 ** -7, atol=1e-6)
+        cu_kv = wl.host_i32(s.cu_kv)
+        lo, hi = cu_kv[req_of_row[rows]], cu_kv[req_of_row[rows] + 1]
+        Or, Lr = oracle.partial_attn(qb, wl.bits(s.k), wl.bits(s.v), qp, wl.host_i32(s.kv_pos), pc.scale, pc.causal, rows, heads, lo, hi)
+        check_o_lse(O.float().cpu().numpy().reshape(-1, D), LSE.cpu().numpy().reshape(-1), Or, Lr, f"{pc.name} shard {si} (retain)")
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (8, 2), (4, 1)])
+def test_retain_striped_varlen_ragged(esp, cuda, Hq, Hkv):
+    pc = wl.striped_prefill(f"retain-varlen-{Hq}/{Hkv}", [1, 63, 257, 300, 64, 700], 2, 0, Hq, Hkv, 120, cuda)
+    run_retain_case(esp, pc, 1)
+
+
+def test_retain_long_shard_plain_iterations_and_fp32_out(esp, cuda):
+    """A chunk behind a long prefix: most tiles run the branch-free iteration, the slot ring wraps several times."""
+    pc = wl.contiguous_prefill("retain-long", 300, 2300, [(0, 2000), (2000, 2600)], 4, 4, 121, cuda)
+    run_retain_case(esp, pc, 2, out_dtype=torch.float32)
+
+
+def test_retain_rows_no_query_can_see(esp, cuda):
+    """The shard lies in the future of every query (and, second shard, of most): everything asked for is kept anyway."""
+    pc = wl.contiguous_prefill("retain-future", 300, 0, [(5000, 5777), (100, 900)], 4, 2, 122, cuda)
+    run_retain_case(esp, pc, 3, keep_fraction=1.0)
+
+
+def test_retain_non_causal_and_unsorted(esp, cuda):
+    pc = wl.contiguous_prefill("retain-noncausal", 130, 0, [(0, 200), (200, 533)], 4, 4, 123, cuda, causal=False)
+    run_retain_case(esp, pc, 4)
+    pc = wl.contiguous_prefill("retain-shuffled", 300, 500, [(0, 450), (450, 1100)], 4, 2, 124, cuda)
+    g = torch.Generator(device="cpu").manual_seed(6)
+    for s in pc.shards:
+        s.kv_pos = s.kv_pos[torch.randperm(s.kv_pos.numel(), generator=g).to(cuda)].contiguous()
+    pc.q_pos = pc.q_pos[torch.randperm(pc.q_pos.numel(), generator=g).to(cuda)].contiguous()
+    run_retain_case(esp, pc, 5)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(4, 2), (8, 8)])
+def test_retain_more_items_than_workgroups(esp, cuda, Hq, Hkv):
+    Tq = 256 * 72 + 40
+    pc = wl.contiguous_prefill(f"retain-many-items-{Hq}/{Hkv}", Tq, 200, [(0, 330), (330, 700)], Hq, Hkv, 125, cuda)
+    pc.q_pos[:] = torch.randint(0, 900, (Tq,), dtype=torch.int32, device=cuda)
+    run_retain_case(esp, pc, 6)
+
+
+def test_retain_requests_without_queries_and_no_queries_at_all(esp, cuda):
+    """A batch whose first and last requests have rows in the shard but no query row in this call: their rows are kept
+    all the same.  Then no query row at all (Tq = 0): the call is a plain scatter."""
+    import dataclasses
+    pc = wl.striped_prefill("retain-noq", [100, 80, 70], 2, 0, 4, 2, 126, cuda)
+    sub = dataclasses.replace(pc, name="retain-noq", q=pc.q[100:180].contiguous(), q_pos=pc.q_pos[100:180].contiguous(),
+                              cu_q=torch.tensor([0, 0, 80, 80], dtype=torch.int32, device=cuda), max_q=80)
+    run_retain_case(esp, sub, 7)
+    none = dataclasses.replace(pc, name="retain-tq0", q=pc.q[:0].contiguous(), q_pos=pc.q_pos[:0].contiguous(),
+                               cu_q=torch.tensor([0, 0, 0, 0], dtype=torch.int32, device=cuda), max_q=0)
+    run_retain_case(esp, none, 8)
