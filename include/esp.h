@@ -309,6 +309,20 @@ esp_status esp_plan_prefill_batches(
     int32_t* split_req, int32_t* split_ins);
 
 /*
+ * The same plan searched with the monotone split points of Eq. 6 (Sec. 5.3): the search for the last batch of
+ * (first i requests, first k instances) starts at split_req[i][k-1] and split_ins[i-1][k] instead of at 0.  The
+ * section states the monotonicity as a property; under the cost read here (see esp_plan_prefill_batches) it holds
+ * in about three random instances in four, so this is a heuristic: the result is a valid plan (a cell with nothing
+ * feasible inside the bounds is searched in full) whose cost is never below the exhaustive search's, equal to it
+ * where the property holds, and up to a few times higher where it does not.  The exhaustive search stays the
+ * default; the section itself calls it fast enough.  Same arguments and outputs.
+ */
+esp_status esp_plan_prefill_batches_monotone(
+    const int64_t* req_len, int32_t n_req, const int64_t* free_slots, int32_t n_inst,
+    const double* coefs, int32_t* req_cuts, int32_t* inst_cuts, int32_t* n_batches, double* cost,
+    int32_t* split_req, int32_t* split_ins);
+
+/*
  * Iteration-time model of the prefill phase (Sec. 5.5 "Optimizations", analytical model based on SIB, Eq. 7):
  *   T(R) = alpha + beta * sum_{r in R} len_r + gamma * sum_{r in R} len_r^2,
  * fitted by least squares to n >= 3 profiled batches (HOST arrays: per batch the two sums and the measured

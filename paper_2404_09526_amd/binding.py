@@ -26,7 +26,7 @@ EXPORTS = (
     "esp_probe_mfma_bf16", "esp_probe_stream_read",
     "esp_partial_attn_prefill_f32", "esp_merge_partials_f32",
     "esp_debug_set_validate", "esp_debug_set_prefill_sync_ticks",
-    "esp_partial_attn_decode_static", "esp_partial_attn_prefill_retain",
+    "esp_partial_attn_decode_static", "esp_partial_attn_prefill_retain", "esp_plan_prefill_batches_monotone",
 )
 ESP_DECODE_STATIC_SCRATCH_BYTES = 32 << 20
 
@@ -80,6 +80,8 @@ def _load() -> ctypes.CDLL:
     L.esp_probe_stream_read.restype = i32
     L.esp_plan_prefill_batches.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp]
     L.esp_plan_prefill_batches.restype = i32
+    L.esp_plan_prefill_batches_monotone.argtypes = L.esp_plan_prefill_batches.argtypes
+    L.esp_plan_prefill_batches_monotone.restype = i32
     L.esp_fit_prefill_model.argtypes = [vp, vp, vp, vp, i32, vp]
     L.esp_fit_prefill_model.restype = i32
     L.esp_last_error.argtypes = []
@@ -401,8 +403,9 @@ def esp_probe_stream_read(src, sink) -> int:
     return nbytes
 
 
-def esp_plan_prefill_batches(req_len, free_slots, coefs, with_tables=False):
-    """Batching plan of the prefill phase (host code).  req_len: tokens per request, longest first; free_slots:
+def esp_plan_prefill_batches(req_len, free_slots, coefs, with_tables=False, monotone=False):
+    """Batching plan of the prefill phase (host code); monotone: the search bounded by the split points of Eq. 6
+    (esp_plan_prefill_batches_monotone: a valid plan, usually but not always the cheapest).  req_len: tokens per request, longest first; free_slots:
     unused KV slots per instance; coefs: [n_inst][3] = (alpha, beta, gamma) at degree of parallelism 1..n_inst.
     Returns (cost, req_cuts, inst_cuts) -- cost inf and empty cuts if nothing fits -- plus the two split tables
     if with_tables."""
@@ -418,8 +421,8 @@ def esp_plan_prefill_batches(req_len, free_slots, coefs, with_tables=False):
     sr = np.zeros((n + 1, m + 1), np.int32) if with_tables else None
     si = np.zeros((n + 1, m + 1), np.int32) if with_tables else None
     p = lambda arr: ctypes.c_void_p(arr.ctypes.data) if arr is not None else ctypes.c_void_p(0)
-    _check(lib.esp_plan_prefill_batches(p(rl), n, p(fs), m, p(cf), p(rc), p(ic), ctypes.addressof(nb),
-                                        ctypes.addressof(cost), p(sr), p(si)))
+    call = lib.esp_plan_prefill_batches_monotone if monotone else lib.esp_plan_prefill_batches
+    _check(call(p(rl), n, p(fs), m, p(cf), p(rc), p(ic), ctypes.addressof(nb), ctypes.addressof(cost), p(sr), p(si)))
     out = (cost.value, rc[:nb.value].tolist(), ic[:nb.value].tolist())
     return out + (sr, si) if with_tables else out
 

@@ -86,9 +86,14 @@ esp_status esp_fit_prefill_model(const double* sum_len, const double* sum_len_sq
     return ESP_OK;
 }
 
-esp_status esp_plan_prefill_batches(const int64_t* req_len, int32_t n_req, const int64_t* free_slots, int32_t n_inst,
-                                    const double* coefs, int32_t* req_cuts, int32_t* inst_cuts, int32_t* n_batches,
-                                    double* cost, int32_t* split_req, int32_t* split_ins) {
+}  // extern "C"
+
+// The dynamic program.  `monotone`: the search for the last batch of (first i requests, first k instances) starts at
+// the split points of its neighbours, split_req[i][k-1] and split_ins[i-1][k] (the lower halves of the two
+// inequalities of Eq. 6, the halves that are known when the table is filled row by row).
+static esp_status plan_batches(const int64_t* req_len, int32_t n_req, const int64_t* free_slots, int32_t n_inst,
+                               const double* coefs, int32_t* req_cuts, int32_t* inst_cuts, int32_t* n_batches,
+                               double* cost, int32_t* split_req, int32_t* split_ins, bool monotone) {
     if (!req_len || !free_slots || !coefs || !req_cuts || !inst_cuts || !n_batches || !cost)
         return fail(ESP_ERR_INVALID_ARG, "plan: null argument");
     if (n_req < 1 || n_inst < 1) return fail(ESP_ERR_INVALID_ARG, "plan: needs at least one request and one instance");
@@ -116,16 +121,27 @@ esp_status esp_plan_prefill_batches(const int64_t* req_len, int32_t n_req, const
     for (int i = 1; i <= n; ++i)
         for (int k = 1; k <= m; ++k) {
             double best = inf; int bj = -1, bl = -1;
-            for (int j = 0; j < i; ++j)                 // the last batch holds requests j .. i-1
-                for (int l = 0; l < k; ++l) {           // on instances l .. k-1
-                    const double prev = f[(size_t)j * W + l];
-                    if (prev == inf) continue;
-                    if (d[i] - d[j] > v[k] - v[l]) continue;
-                    const double* c = coefs + 3 * (size_t)(k - l - 1);
-                    const double t = c[0] + c[1] * (s1[i] - s1[j]) + c[2] * (s2[i] - s2[j]);
-                    const double total = prev + t * (sinv[i] - sinv[j]);
-                    if (total < best) { best = total; bj = j; bl = l; }
+            int j0 = 0, l0 = 0;
+            if (monotone) {
+                if (k > 1 && sr[(size_t)i * W + k - 1] >= 0) j0 = sr[(size_t)i * W + k - 1];
+                if (i > 1 && si[(size_t)(i - 1) * W + k] >= 0) l0 = si[(size_t)(i - 1) * W + k];
+            }
+            for (int pass = 0; pass < 2 && best == inf; ++pass) {
+                if (pass == 1) {                        // nothing fits inside the bounds: search the whole range
+                    if (j0 == 0 && l0 == 0) break;
+                    j0 = 0; l0 = 0;
                 }
+                for (int j = j0; j < i; ++j)            // the last batch holds requests j .. i-1
+                    for (int l = l0; l < k; ++l) {      // on instances l .. k-1
+                        const double prev = f[(size_t)j * W + l];
+                        if (prev == inf) continue;
+                        if (d[i] - d[j] > v[k] - v[l]) continue;
+                        const double* c = coefs + 3 * (size_t)(k - l - 1);
+                        const double t = c[0] + c[1] * (s1[i] - s1[j]) + c[2] * (s2[i] - s2[j]);
+                        const double total = prev + t * (sinv[i] - sinv[j]);
+                        if (total < best) { best = total; bj = j; bl = l; }
+                    }
+            }
             f[(size_t)i * W + k] = best; sr[(size_t)i * W + k] = bj; si[(size_t)i * W + k] = bl;
         }
     if (split_req) for (size_t t = 0; t < sr.size(); ++t) split_req[t] = sr[t];
@@ -148,6 +164,20 @@ esp_status esp_plan_prefill_batches(const int64_t* req_len, int32_t n_req, const
     }
     *n_batches = nb;
     return ESP_OK;
+}
+
+extern "C" {
+
+esp_status esp_plan_prefill_batches(const int64_t* req_len, int32_t n_req, const int64_t* free_slots, int32_t n_inst,
+                                    const double* coefs, int32_t* req_cuts, int32_t* inst_cuts, int32_t* n_batches,
+                                    double* cost, int32_t* split_req, int32_t* split_ins) {
+    return plan_batches(req_len, n_req, free_slots, n_inst, coefs, req_cuts, inst_cuts, n_batches, cost, split_req, split_ins, false);
+}
+
+esp_status esp_plan_prefill_batches_monotone(const int64_t* req_len, int32_t n_req, const int64_t* free_slots, int32_t n_inst,
+                                             const double* coefs, int32_t* req_cuts, int32_t* inst_cuts, int32_t* n_batches,
+                                             double* cost, int32_t* split_req, int32_t* split_ins) {
+    return plan_batches(req_len, n_req, free_slots, n_inst, coefs, req_cuts, inst_cuts, n_batches, cost, split_req, split_ins, true);
 }
 
 }  // extern "C"

@@ -110,3 +110,41 @@ def test_fit_matches_library_least_squares():
     assert esp.esp_fit_prefill_model([0.0, 1.0, 2.0], [0.0, 0.0, 0.0], [1.0, 3.0, 5.0]) == pytest.approx([1.0, 2.0, 0.0])
     with pytest.raises(esp.EspError):
         esp.esp_fit_prefill_model([1.0, 2.0], [1.0, 4.0], [1.0, 2.0])
+
+
+def test_search_bounded_by_the_monotone_split_points():
+    """esp_plan_prefill_batches_monotone (Eq. 6 as search bounds): feasible exactly when the full search is, the plan
+    valid and priced to the reported cost, the cost never below the full search's; how often it is equal is printed
+    (the monotonicity is a property the section states; the cost as read here has it in about three instances in
+    four, with or without pressure on the slots, and where it fails the bounded plan can cost a multiple)."""
+    import time
+    rng = np.random.default_rng(77)
+    same = worse = infeasible = 0
+    worst = 1.0
+    for _ in range(600):
+        lens, slots, coefs = random_instance(rng, n_max=9, m_max=6)
+        cost, rc, ic = esp.esp_plan_prefill_batches(lens, slots, coefs)
+        cm, rcm, icm = esp.esp_plan_prefill_batches(lens, slots, coefs, monotone=True)
+        if cost == float("inf"):
+            assert cm == float("inf") and rcm == []
+            infeasible += 1
+            continue
+        assert cm < float("inf")
+        assert rcm[-1] == len(lens) and icm[-1] <= len(slots) and len(rcm) == len(icm)
+        assert oplan.plan_cost(lens, slots, coefs, rcm, icm) == pytest.approx(cm, rel=1e-12)
+        assert cm >= cost * (1 - 1e-12)
+        if cm <= cost * (1 + 1e-12):
+            same += 1
+        else:
+            worse += 1
+            worst = max(worst, cm / cost)
+    print(f"[case] monotone search: {same} of {same + worse} feasible instances at the optimum, worst ratio {worst:.4f}; {infeasible} infeasible")
+    assert same >= 0.6 * (same + worse)          # measured: three in four; a guard against a broken bound, not a claim
+    # a scheduler-sized instance: both searches, wall time
+    lens = sorted((int(x) for x in rng.integers(64, 200000, 256)), reverse=True)
+    slots = [int(x) for x in rng.integers(200000, 4000000, 16)]
+    coefs = [(2e-5 * (1 + 0.2 * d), 6e-9 / d ** 0.9, 6e-12 / d ** 0.8) for d in range(1, 17)]
+    t0 = time.perf_counter(); c0, _, _ = esp.esp_plan_prefill_batches(lens, slots, coefs); t1 = time.perf_counter()
+    c1, _, _ = esp.esp_plan_prefill_batches(lens, slots, coefs, monotone=True); t2 = time.perf_counter()
+    print(f"[case] 256 requests on 16 instances: full search {1e3 * (t1 - t0):.2f} ms (cost {c0:.6g}), bounded {1e3 * (t2 - t1):.2f} ms (cost {c1:.6g})")
+    assert c1 >= c0 * (1 - 1e-12)
