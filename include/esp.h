@@ -170,6 +170,31 @@ esp_status esp_partial_attn_decode_static(
     void* O, float* LSE, void* stream);
 
 /*
+ * The master's step of a multi-master decode (Sec. 4.2): its local partial
+ * attention over the token pool, combined in the same pass with the partial
+ * results its peers sent back for the same queries (the combination stated
+ * below for esp_merge_partials, with the local result as one more partial).
+ * The local result is never rounded to bf16 on its own and no separate merge
+ * launch follows.  Arguments as esp_partial_attn_decode, plus
+ *   peer_O   : HOST array of n_peers DEVICE pointers, each bf16 [B, Hq, D];
+ *   peer_LSE : HOST array of n_peers DEVICE pointers, each fp32 [B, Hq];
+ *   n_peers  : 0 .. ESP_MAX_PARTIALS - 1 (0: plain esp_partial_attn_decode).
+ * The pointer arrays are read during the call only.  O / LSE receive the
+ * FINAL result and must not overlap a peer's arrays (ESP_ERR_INVALID_ARG).
+ * A master that holds no token of a request (seq_offsets[b+1] ==
+ * seq_offsets[b]) passes its peers' combination through.  Errors as
+ * esp_partial_attn_decode.
+ */
+esp_status esp_partial_attn_decode_merge(
+    const void* q, const void* k_pool, const void* v_pool, int64_t num_slots,
+    const int32_t* slot_idx, const int32_t* seq_offsets, int32_t B,
+    int32_t total_tokens, int32_t max_len,
+    int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale,
+    const void* const* peer_O, const float* const* peer_LSE, int32_t n_peers,
+    void* O, float* LSE,
+    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Combination of partial results ("generate the final output", Sec. 2.3;
  * results "sent back to the master", Sec. 4.2).  For each (token, head):
  *   m = max_p LSE_p,  w_p = exp(LSE_p - m),

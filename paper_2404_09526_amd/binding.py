@@ -27,6 +27,7 @@ EXPORTS = (
     "esp_partial_attn_prefill_f32", "esp_merge_partials_f32",
     "esp_debug_set_validate", "esp_debug_set_prefill_sync_ticks",
     "esp_partial_attn_decode_static", "esp_partial_attn_prefill_retain", "esp_plan_prefill_batches_monotone",
+    "esp_partial_attn_decode_merge",
 )
 ESP_DECODE_STATIC_SCRATCH_BYTES = 32 << 20
 
@@ -60,6 +61,9 @@ def _load() -> ctypes.CDLL:
     L.esp_prefill_workspace_bytes.restype = sz
     L.esp_partial_attn_decode.argtypes = [vp, vp, vp, i64, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, vp, vp, sz, vp]
     L.esp_partial_attn_decode.restype = i32
+    L.esp_partial_attn_decode_merge.argtypes = [vp, vp, vp, i64, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, vp, i32,
+                                                vp, vp, vp, sz, vp]
+    L.esp_partial_attn_decode_merge.restype = i32
     L.esp_partial_attn_decode_static.argtypes = [vp, vp, vp, i64, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, vp, vp]
     L.esp_partial_attn_decode_static.restype = i32
     L.esp_decode_workspace_bytes.argtypes = [i32] * 6
@@ -279,6 +283,41 @@ def esp_partial_attn_decode_static(q, k_pool, v_pool, slot_idx, seq_offsets, max
     _check(lib.esp_partial_attn_decode_static(_ptr(q), _ptr(k_pool), _ptr(v_pool), S, _ptr(slot_idx), _ptr(seq_offsets), B,
                                               slot_idx.numel(), int(max_len), Hq, Hkv, D, float(softmax_scale), _ptr(O), _ptr(LSE),
                                               _stream()))
+    return O, LSE
+
+
+def esp_partial_attn_decode_merge(q, k_pool, v_pool, slot_idx, seq_offsets, max_len, peer_O: Sequence[torch.Tensor],
+                                  peer_LSE: Sequence[torch.Tensor], softmax_scale=None, O=None, LSE=None, workspace=None):
+    """esp_partial_attn_decode combined, in the same pass, with the partial results peers returned for the same
+    queries (peer_O[p] bf16 [B,Hq,D], peer_LSE[p] fp32 [B,Hq]).  Returns the final (O bf16, LSE fp32)."""
+    _dev(q, torch.bfloat16, "q"); _dev(k_pool, torch.bfloat16, "k_pool"); _dev(v_pool, torch.bfloat16, "v_pool")
+    _dev(slot_idx, torch.int32, "slot_idx"); _dev(seq_offsets, torch.int32, "seq_offsets")
+    B, Hq, D = q.shape
+    S, Hkv, Dk = k_pool.shape
+    if v_pool.shape != k_pool.shape or Dk != D or seq_offsets.numel() != B + 1:
+        raise ValueError("decode: shape mismatch")
+    P = len(peer_O)
+    if P != len(peer_LSE):
+        raise ValueError("decode (merge): peer_O and peer_LSE differ in length")
+    for i in range(P):
+        _dev(peer_O[i], torch.bfloat16, f"peer_O[{i}]"); _dev(peer_LSE[i], torch.float32, f"peer_LSE[{i}]")
+        if peer_O[i].shape != q.shape or peer_LSE[i].shape != (B, Hq):
+            raise ValueError("decode (merge): peer partial shapes differ from the queries'")
+    total = slot_idx.numel()
+    if softmax_scale is None:
+        softmax_scale = D ** -0.5
+    if O is None:
+        O = torch.empty_like(q)
+    if LSE is None:
+        LSE = torch.empty((B, Hq), dtype=torch.float32, device=q.device)
+    _dev(O, torch.bfloat16, "O"); _dev(LSE, torch.float32, "LSE")
+    if workspace is None:
+        workspace = _workspace(esp_decode_workspace_bytes(B, total, int(max_len), Hq, Hkv, D), q.device)
+    op = (ctypes.c_void_p * max(P, 1))(*[t.data_ptr() for t in peer_O])
+    lp = (ctypes.c_void_p * max(P, 1))(*[t.data_ptr() for t in peer_LSE])
+    _check(lib.esp_partial_attn_decode_merge(_ptr(q), _ptr(k_pool), _ptr(v_pool), S, _ptr(slot_idx), _ptr(seq_offsets), B,
+                                             total, int(max_len), Hq, Hkv, D, float(softmax_scale), op, lp, P,
+                                             _ptr(O), _ptr(LSE), _ptr(workspace), workspace.numel(), _stream()))
     return O, LSE
 
 

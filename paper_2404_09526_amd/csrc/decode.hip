@@ -381,10 +381,16 @@ __global__ __launch_bounds__(kDecWaves * 64) void decode_partial_any_kernel(
 
 // One workgroup per (request, head): 4 groups of 64 lanes split the partials, each lane owns
 // two output elements; the groups are then combined through LDS.
+//
+// PEERS: the master of a multi-master decode (Sec. 4.2) also holds the partial results its peers returned for the
+// same queries (bf16 O, natural-log LSE).  They enter the same log-sum-exp combination here, so the local result is
+// never rounded to bf16 on its own and no separate merge launch follows.
+template <bool PEERS>
 __global__ __launch_bounds__(256) void decode_combine_kernel(const int32_t* __restrict__ seq_offsets,
                                                              int32_t range, int32_t nt, int32_t Hq,
                                                              const float* __restrict__ part_acc,
                                                              const float* __restrict__ part_ml,
+                                                             MergeArgs peers, int32_t n_peers,
                                                              uint32_t* __restrict__ O, float* __restrict__ LSE) {
     const int b = blockIdx.x / Hq, h = blockIdx.x % Hq;
     const int dp = threadIdx.x & 63, grp = threadIdx.x >> 6;
@@ -413,6 +419,15 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(const int32_t* __re
     __syncthreads();
     if (grp == 0) {
         float mx = fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
+        const int64_t pair = (int64_t)b * Hq + h;
+        float lse_p[ESP_MAX_PARTIALS];                            // the peers' LSE in base-2 units, like mx
+        if (PEERS) {
+#pragma unroll
+            for (int p = 0; p < ESP_MAX_PARTIALS; ++p) {
+                lse_p[p] = (p < n_peers) ? peers.LSE_parts[p][pair] * kLog2e : -INFINITY;
+                mx = fmaxf(mx, lse_p[p]);
+            }
+        }
         float Lt = 0.f, o0 = 0.f, o1 = 0.f;
         if (mx != -INFINITY) {
 #pragma unroll
@@ -422,11 +437,25 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(const int32_t* __re
                 o0 += sa[g][dp * 2] * c;
                 o1 += sa[g][dp * 2 + 1] * c;
             }
+            if (PEERS) {
+#pragma unroll
+                for (int p = 0; p < ESP_MAX_PARTIALS; ++p) {
+                    if (p < n_peers) {
+                        const float w = __builtin_amdgcn_exp2f(lse_p[p] - mx);   // a peer's rows are normalised: mass w
+                        const uint32_t o = ((const uint32_t*)peers.O_parts[p])[pair * (kHeadDim / 2) + dp];
+                        if (w != 0.f) {                           // keeps the garbage of an empty partial out of the sum
+                            Lt += w;
+                            o0 += w * bf16_lo(o);
+                            o1 += w * bf16_hi(o);
+                        }
+                    }
+                }
+            }
             float inv = 1.0f / Lt;
             o0 *= inv; o1 *= inv;
         }
-        O[((int64_t)b * Hq + h) * (kHeadDim / 2) + dp] = pack_bf16(o0, o1);
-        if (dp == 0) LSE[(int64_t)b * Hq + h] = (mx == -INFINITY) ? -INFINITY : (mx + __builtin_amdgcn_logf(Lt)) * kLn2;
+        O[pair * (kHeadDim / 2) + dp] = pack_bf16(o0, o1);
+        if (dp == 0) LSE[pair] = (mx == -INFINITY) ? -INFINITY : (mx + __builtin_amdgcn_logf(Lt)) * kLn2;
     }
 }
 
@@ -447,7 +476,7 @@ esp_status launch_decode_static(const void* q, const void* k_pool, const void* v
 esp_status launch_decode(const void* q, const void* k_pool, const void* v_pool, const int32_t* slot_idx,
                          const int32_t* seq_offsets, int32_t B, int32_t total_tokens, int32_t Hq, int32_t Hkv,
                          float softmax_scale, void* O, float* LSE, void* workspace, size_t workspace_bytes,
-                         hipStream_t stream) {
+                         hipStream_t stream, const MergeArgs* peers, int32_t n_peers) {
     (void)workspace_bytes;
     DecodeGeom g = decode_geom(total_tokens, Hq, Hkv);
     size_t n = decode_slots(g, B) * (size_t)g.nt * (size_t)Hq;
@@ -490,8 +519,13 @@ esp_status launch_decode(const void* q, const void* k_pool, const void* v_pool, 
         esp_status st = check_launch("decode_partial_kernel");
         if (st != ESP_OK) return st;
     }
-    hipLaunchKernelGGL(decode_combine_kernel, dim3((unsigned)((int64_t)B * Hq)), dim3(256), 0, stream, seq_offsets,
-                       g.range, g.nt, Hq, (const float*)part_acc, (const float*)part_ml, (uint32_t*)O, LSE);
+    const dim3 cgrid((unsigned)((int64_t)B * Hq));
+    if (peers != nullptr && n_peers > 0)
+        hipLaunchKernelGGL(decode_combine_kernel<true>, cgrid, dim3(256), 0, stream, seq_offsets, g.range, g.nt, Hq,
+                           (const float*)part_acc, (const float*)part_ml, *peers, n_peers, (uint32_t*)O, LSE);
+    else
+        hipLaunchKernelGGL(decode_combine_kernel<false>, cgrid, dim3(256), 0, stream, seq_offsets, g.range, g.nt, Hq,
+                           (const float*)part_acc, (const float*)part_ml, MergeArgs{}, 0, (uint32_t*)O, LSE);
     return check_launch("decode_combine_kernel");
 }
 

@@ -287,6 +287,44 @@ esp_status esp_partial_attn_decode_static(const void* q, const void* k_pool, con
                                 (hipStream_t)stream);
 }
 
+esp_status esp_partial_attn_decode_merge(const void* q, const void* k_pool, const void* v_pool, int64_t num_slots,
+                                         const int32_t* slot_idx, const int32_t* seq_offsets, int32_t B,
+                                         int32_t total_tokens, int32_t max_len, int32_t Hq, int32_t Hkv, int32_t D,
+                                         float softmax_scale, const void* const* peer_O, const float* const* peer_LSE,
+                                         int32_t n_peers, void* O, float* LSE, void* workspace, size_t workspace_bytes,
+                                         void* stream) {
+    if (n_peers < 0 || n_peers > ESP_MAX_PARTIALS - 1)
+        return fail(ESP_ERR_INVALID_ARG, "decode (merge): n_peers=%d outside 0..%d", n_peers, ESP_MAX_PARTIALS - 1);
+    bool done;
+    esp_status st = decode_check(q, k_pool, v_pool, num_slots, slot_idx, seq_offsets, B, total_tokens, max_len, Hq, Hkv, D,
+                                 softmax_scale, O, LSE, &done);
+    if (st != ESP_OK || done) return st;
+    MergeArgs peers = {};
+    if (n_peers > 0) {
+        if (!peer_O || !peer_LSE) return fail(ESP_ERR_INVALID_ARG, "decode (merge): null pointer arrays");
+        const size_t o_bytes = (size_t)B * Hq * kHeadDim * 2, l_bytes = (size_t)B * Hq * 4;
+        for (int p = 0; p < n_peers; ++p) {
+            if (!peer_O[p] || !peer_LSE[p]) return fail(ESP_ERR_INVALID_ARG, "decode (merge): null partial %d", p);
+            if (((uintptr_t)peer_O[p] & 3) || ((uintptr_t)peer_LSE[p] & 3))
+                return fail(ESP_ERR_INVALID_ARG, "decode (merge): partial %d not 4-byte aligned", p);
+            const char *a = (const char*)peer_O[p], *b = (const char*)peer_LSE[p];
+            if ((a < (const char*)O + o_bytes && (const char*)O < a + o_bytes) ||
+                (b < (const char*)LSE + l_bytes && (const char*)LSE < b + l_bytes))
+                return fail(ESP_ERR_INVALID_ARG, "decode (merge): the output overlaps partial %d", p);
+            peers.O_parts[p] = peer_O[p];
+            peers.LSE_parts[p] = peer_LSE[p];
+        }
+    }
+    size_t need = decode_workspace_bytes(B, total_tokens, Hq, Hkv);
+    if (!workspace || workspace_bytes < need)
+        return fail(ESP_ERR_WORKSPACE, "decode: workspace needs %zu bytes, got %zu", need, workspace ? workspace_bytes : (size_t)0);
+    if ((uintptr_t)workspace & 255) return fail(ESP_ERR_WORKSPACE, "decode: workspace not 256-byte aligned");
+    st = decode_validate(slot_idx, seq_offsets, B, total_tokens, max_len, num_slots, stream);
+    if (st != ESP_OK) return st;
+    return launch_decode(q, k_pool, v_pool, slot_idx, seq_offsets, B, total_tokens, Hq, Hkv, softmax_scale, O, LSE,
+                         workspace, workspace_bytes, (hipStream_t)stream, &peers, n_peers);
+}
+
 static esp_status merge_entry(const void* const* O_parts, const float* const* LSE_parts, int32_t P, int32_t T,
                               int32_t Hq, int32_t D, int32_t parts_f32, void* O, float* LSE_out, void* stream) {
     if (P < 1 || P > ESP_MAX_PARTIALS) return fail(ESP_ERR_INVALID_ARG, "merge: P=%d outside 1..%d", P, ESP_MAX_PARTIALS);

@@ -54,7 +54,7 @@ size_t decode_workspace_bytes(int32_t B, int32_t total_tokens, int32_t Hq, int32
 esp_status launch_decode(const void* q, const void* k_pool, const void* v_pool, const int32_t* slot_idx,
                          const int32_t* seq_offsets, int32_t B, int32_t total_tokens, int32_t Hq, int32_t Hkv,
                          float softmax_scale, void* O, float* LSE, void* workspace, size_t workspace_bytes,
-                         hipStream_t stream);
+                         hipStream_t stream, const MergeArgs* peers = nullptr, int32_t n_peers = 0);
 
 int32_t set_prefill_sync_ticks(int32_t ticks);   // returns the previous value; negative restores the built-in default
 esp_status launch_decode_static(const void* q, const void* k_pool, const void* v_pool, const int32_t* slot_idx,

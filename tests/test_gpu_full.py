@@ -192,6 +192,14 @@ def check_decode_sampled(esp, dc, sample, heads_per_req=None):
     Oref, Lref = oracle.merge_partials(Op, Lp)
     check_o_lse(Om.float().cpu().numpy().reshape(-1, dc.D), Lm.cpu().numpy().reshape(-1), Oref.reshape(-1, dc.D),
                 Lref.reshape(-1), f"{dc.name} merge")
+    # the same step as one call (what the benchmark times): the oracle's OWN local partials, never rounded, with the peers
+    Of, Lf = esp.esp_partial_attn_decode_merge(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, int(dc.lens.max()),
+                                               list(dc.peer_O), list(dc.peer_LSE), softmax_scale=dc.scale)
+    torch.cuda.synchronize()
+    Op = np.stack([Or] + [oracle.bf16_bits_to_f64(wl.bits(t))[reqs, hs] for t in dc.peer_O])
+    Lp = np.stack([Lr] + [t.cpu().numpy().astype(np.float64)[reqs, hs] for t in dc.peer_LSE])
+    Oref, Lref = oracle.merge_partials(Op, Lp)
+    check_o_lse(Of.float().cpu().numpy()[reqs, hs], Lf.cpu().numpy()[reqs, hs], Oref, Lref, f"{dc.name} decode + merge in one call")
     # append to random free slots: appended rows + 4096 random untouched rows on the host, whole-pool checksum on device
     new_slots = wl.host_i32(dc.new_slots)
     rng = np.random.default_rng(7)

@@ -302,6 +302,47 @@ def test_decode_mqa_many_ranges_and_merge(esp, cuda):
     check_o_lse(Om.float().cpu().numpy().reshape(-1, 128), Lm.cpu().numpy().reshape(-1), Oref.reshape(-1, 128), Lref.reshape(-1), "MQA merge")
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(8, 4), (6, 3), (32, 32)])
+def test_decode_merged_with_the_peers_partials_in_one_pass(esp, cuda, Hq, Hkv):
+    """The master's step of a multi-master decode (Sec. 4.2): local partial attention and the combination with the
+    peers' results in one call, against the oracle's merge of ITS OWN local partial (fp64, never rounded) with the same
+    peer arrays.  Covers a request the master holds nothing of, a peer that holds nothing of a request (LSE = -inf, O
+    garbage), a request nobody holds anything of, and n_peers = 0 (bit-identical to the plain call)."""
+    lens = [300, 0, 1500, 64, 0, 2200, 9, 1]
+    dc = wl.decode_pool(f"decode-merge-{Hq}/{Hkv}", lens, 8192, Hq, Hkv, 37, cuda, n_new=0)
+    O_loc, L_loc, kp, vp = run_decode_case(esp, dc)
+    peers_O = [t.clone() for t in dc.peer_O]; peers_L = [t.clone() for t in dc.peer_LSE]
+    peers_L[1][2] = float("-inf"); peers_O[1][2] = float("nan")          # a peer without tokens of request 2
+    for t_o, t_l in zip(peers_O, peers_L):                                # nobody holds a token of request 4
+        t_l[4] = float("-inf"); t_o[4] = float("nan")
+    O, LSE = esp.esp_partial_attn_decode_merge(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, int(dc.lens.max()),
+                                               peers_O, peers_L, softmax_scale=dc.scale)
+    torch.cuda.synchronize()
+    off, slots = wl.host_i32(dc.seq_offsets), wl.host_i32(dc.slot_idx)
+    Or, Lr = oracle.partial_attn_decode_all(wl.bits(dc.q), kp, vp, slots, off, dc.scale)
+    Op = np.stack([Or] + [np.nan_to_num(oracle.bf16_bits_to_f64(wl.bits(t)), nan=0.0) for t in peers_O])
+    Lp = np.stack([Lr] + [t.cpu().numpy().astype(np.float64) for t in peers_L])
+    Oref, Lref = oracle.merge_partials(Op, Lp)
+    check_o_lse(O.float().cpu().numpy().reshape(-1, dc.D), LSE.cpu().numpy().reshape(-1), Oref.reshape(-1, dc.D),
+                Lref.reshape(-1), f"{dc.name} local + {len(peers_O)} peers")
+    assert torch.isneginf(LSE[4]).all() and (O[4] == 0).all()
+    assert torch.isfinite(O.float()).all()
+    # request 1: the master holds nothing, so the result is the peers' combination alone
+    Om, Lm = esp.esp_merge_partials([t[1:2].contiguous() for t in peers_O], [t[1:2].contiguous() for t in peers_L])
+    torch.cuda.synchronize()
+    assert torch.allclose(O[1:2].float(), Om.float(), rtol=2 ** -7, atol=1e-6) and torch.allclose(LSE[1:2], Lm, rtol=1e-6, atol=1e-6)
+    # no peers: the plain call
+    O0, L0 = esp.esp_partial_attn_decode_merge(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, int(dc.lens.max()),
+                                               [], [], softmax_scale=dc.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(O0.view(torch.int16), O_loc.view(torch.int16)) and torch.equal(L0.view(torch.int32), L_loc.view(torch.int32))
+    # an output that overlaps a peer's array is refused
+    with pytest.raises(esp.EspError) as e:
+        esp.esp_partial_attn_decode_merge(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, int(dc.lens.max()),
+                                          peers_O, peers_L, softmax_scale=dc.scale, O=peers_O[0])
+    assert e.value.status == esp.ESP_ERR_INVALID_ARG
+
+
 def test_decode_many_ranges(esp, cuda):
     """Enough tokens that the token list is cut into many ranges, with requests spanning several of them."""
     lens = wl.lognormal_lengths(24, 3000, 10, 40000, 31)
