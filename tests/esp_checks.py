@@ -1,10 +1,14 @@
 """Comparison helpers for the parity tests (HIP path vs CPU oracle).  Not a test module.
 
 Tolerances (bf16 output, fp32 accumulation):
-  O    |dO| <= max(1e-2, 2^-8 * |O_ref|) element-wise: the stated max-abs 1e-2 wherever |O_ref| <= 2.56; above
-       that the bf16 output format alone rounds by up to 2^-9 * |O| (0.0156 at |O| = 4, reached by rows that
-       see only a few N(0,1) value rows), so there the bound is the format's own (one ulp).  How many compared
-       elements fell into that scaled region is returned (`o_scaled`) and printed.  AND per (row, head)
+  O    |dO| <= 1e-2 element-wise, the stated max-abs, wherever |O_ref| <= 2.56; above that the bf16 output format
+       alone rounds by up to half a unit in the last place, which is 2^-8 * |O| for a value just above a power of
+       two (0.0156 at |O| = 4.0, reached by rows that see only a few N(0,1) value rows), and the value that gets
+       rounded already carries the rounding of the probabilities to bf16 before the second product, half a unit
+       each, 2^-9 relative: there the bound is (2^-8 + 2^-9) * |O_ref|.  (With 2^-8 alone, an element whose exact
+       value sits just above 4 and whose rounding goes the wrong way fails by the few 1e-4 of error it had before
+       the rounding: seen once, at 1.024 x that bound.)  How many compared elements fell into the scaled
+       region is returned (`o_scaled`) and printed.  AND per (row, head)
        max|dO| <= 2^-7 * max|O_ref| + 1e-5 and cosine >= 0.999 (these keep the test meaningful for long KV,
        where |O| ~ 1/sqrt(n) is tiny and an all-zero output would pass the absolute bound): 2^-8 for the one
        rounding of the output to bf16, another 2^-8 for the bf16 probabilities of the second product.  Every
@@ -15,7 +19,8 @@ Tolerances (bf16 output, fp32 accumulation):
 import numpy as np
 
 O_ABS_TOL = 1e-2
-O_REL_UNIT = 2.0 ** -8
+O_REL_UNIT = 2.0 ** -8             # one rounding to bf16, worst case relative to the value
+O_ELEM_UNIT = 1.5 * 2.0 ** -8      # element-wise: the output's rounding plus the probabilities'
 LSE_REL_TOL = 1e-4
 
 
@@ -35,9 +40,10 @@ def check_o_lse(O_gpu, LSE_gpu, O_ref, LSE_ref, what=""):
     assert (dl <= lim).all(), f"{what}: LSE error {dl.max():.3e} (worst ratio {np.max(dl / lim):.2f})"
     dO = np.abs(O_gpu[fin] - O_ref[fin])
     o_abs = dO.max()
-    o_lim = np.maximum(O_ABS_TOL, O_REL_UNIT * np.abs(O_ref[fin]))
+    a_ref = np.abs(O_ref[fin])
+    o_lim = np.where(a_ref <= O_ABS_TOL / O_REL_UNIT, O_ABS_TOL, O_ELEM_UNIT * a_ref)
     worst = np.max(dO / o_lim)
-    assert worst <= 1.0, f"{what}: O error {worst:.3f} x the bound max(1e-2, 2^-8 |O_ref|); max-abs {o_abs:.3e}"
+    assert worst <= 1.0, f"{what}: O error {worst:.3f} x the bound (1e-2, or 1.5 * 2^-8 |O_ref| above |O_ref| = 2.56); max-abs {o_abs:.3e}"
     o_scaled = int((o_lim > O_ABS_TOL).sum())
     row_ref = np.abs(O_ref[fin]).max(axis=1)
     row_err = dO.max(axis=1)
@@ -49,5 +55,5 @@ def check_o_lse(O_gpu, LSE_gpu, O_ref, LSE_ref, what=""):
     assert (num[ok] / den[ok] >= 0.999).all(), f"{what}: cosine similarity {np.min(num[ok] / den[ok]):.5f}"
     st = dict(o_abs=float(o_abs), lse_err=float(dl.max()), o_scaled=o_scaled, o_compared=int(dO.size))
     print(f"[check] {what}: max|dO| {st['o_abs']:.2e} over {st['o_compared']} elements ({o_scaled} of them above |O_ref| = 2.56, "
-          f"bound 2^-8 |O_ref| there), max|dLSE| {st['lse_err']:.2e} over {int(fin.sum())} rows", flush=True)
+          f"bound 1.5 * 2^-8 |O_ref| there), max|dLSE| {st['lse_err']:.2e} over {int(fin.sum())} rows", flush=True)
     return st
