@@ -49,7 +49,9 @@ def parse():
                          "then decodes those and sends their results back; reports the time against one decode call over all")
     ap.add_argument("--from-pool", action="store_true",
                     help="prefill over pool-resident shards: every shard's rows sit at random slots of a token pool and are "
-                         "attended through esp_partial_attn_prefill_pool; reports the overhead against the dense call")
+                         "attended through esp_partial_attn_prefill_pool (gather into staging rows, then the dense kernel) and through "
+                         "esp_partial_attn_prefill_pool_direct (the tile transfers read the pool rows); reports both overheads "
+                         "against the dense call")
     ap.add_argument("--fit-model", action="store_true",
                     help="also time whole-request causal prefill batches of several length mixes, fit the iteration-time model "
                          "(alpha + beta*sum(len) + gamma*sum(len^2)) with esp_fit_prefill_model and report its error")
@@ -496,9 +498,17 @@ def main():
         pool_O = [torch.empty_like(pc.q) for _ in part_O]; pool_L = [torch.empty_like(x) for x in part_L]
         dense_O = [torch.empty_like(pc.q) for _ in part_O]
 
+        direct_O = [torch.empty_like(pc.q) for _ in part_O]; direct_L = [torch.empty_like(x) for x in part_L]
+
         def prefill_all(from_pool):
             for i, s in enumerate(pc.shards):
-                if from_pool:
+                if from_pool == "direct":
+                    esp.esp_partial_attn_prefill_pool_direct(pc.q, kp, vp, slots[i], pc.q_pos, s.kv_pos,
+                                                             None if single else pc.cu_q, None if single else s.cu_kv,
+                                                             None if single else pc.max_q, None if single else s.max_kv,
+                                                             softmax_scale=pc.scale, causal=pc.causal, O=direct_O[i], LSE=direct_L[i],
+                                                             workspace=ws_pf)
+                elif from_pool:
                     esp.esp_partial_attn_prefill_pool(pc.q, kp, vp, slots[i], pc.q_pos, s.kv_pos,
                                                       None if single else pc.cu_q, None if single else s.cu_kv,
                                                       None if single else pc.max_q, None if single else s.max_kv,
@@ -511,7 +521,7 @@ def main():
                                                  softmax_scale=pc.scale, causal=pc.causal, O=dense_O[i], LSE=part_L[i], workspace=ws_pf)
 
         times = {}
-        for mode in (False, True, False, True):
+        for mode in (False, True, "direct", False, True, "direct"):
             prefill_all(mode); torch.cuda.synchronize()
             e0, e1 = ev(), ev()
             e0.record()
@@ -519,12 +529,15 @@ def main():
                 prefill_all(mode)
             e1.record(); torch.cuda.synchronize()
             times.setdefault(mode, []).append(e0.elapsed_time(e1) / args.steps)
-        t_dense, t_pool = min(times[False]), min(times[True])
+        t_dense, t_pool, t_direct = min(times[False]), min(times[True]), min(times["direct"])
+        same_direct = all(torch.equal(a_, b_) for a_, b_ in zip(dense_O, direct_O)) and all(torch.equal(a_, b_) for a_, b_ in zip(part_L, direct_L))
         same = all(torch.equal(a_, b_) for a_, b_ in zip(dense_O, pool_O)) and all(torch.equal(a_, b_) for a_, b_ in zip(part_L, pool_L))
         moved = 2 * 2 * n_rows * pc.Hkv * pc.D * 2                  # K and V, read from the pool and written to the staging rows
         result["from_pool"] = {"ms_dense": t_dense, "ms_from_pool": t_pool, "overhead_pct": 100.0 * (t_pool / t_dense - 1.0),
                                "rows": n_rows, "gather_bytes": moved, "gather_gbs": moved / ((t_pool - t_dense) * 1e-3) / 1e9,
-                               "same_bits_as_dense": bool(same)}
+                               "same_bits_as_dense": bool(same),
+                               "ms_direct": t_direct, "direct_overhead_pct": 100.0 * (t_direct / t_dense - 1.0),
+                               "direct_same_bits_as_dense": bool(same_direct)}
     if args.workload == "lwm7b" and os.path.exists(args.traffic_json):
         tr = json.load(open(args.traffic_json))
         result["roofline"]["traffic"] = tr.get("prefill_kernel")

@@ -299,6 +299,28 @@ size_t esp_prefill_pool_workspace_bytes(int32_t Tq, int32_t Tkv, int32_t batch,
                                         int32_t Hq, int32_t Hkv, int32_t D);
 
 /*
+ * The same without staging: the kernel's tile transfers take every row from
+ * its pool slot (the slots of a tile travel to on-chip memory one step ahead
+ * of the tile, each lane forms the address of the row its 16 bytes belong
+ * to), so nothing is copied first and the workspace is the dense call's,
+ * esp_prefill_workspace_bytes(...).  Sec. 4.1 / 4.2: key-value rows that an
+ * instance kept stay at the slots they were placed in.  Arguments as
+ * esp_partial_attn_prefill_pool, plus out_f32 (0: O is bf16; else fp32, as in
+ * esp_partial_attn_prefill_f32).  Every slot_idx[i] must lie in
+ * [0, num_slots): the kernel trusts it (checked on the host only while
+ * esp_debug_set_validate is on).  Results equal those of the staged call up to
+ * the order of fp32 additions (the same bound against the exact result holds).
+ */
+esp_status esp_partial_attn_prefill_pool_direct(
+    const void* q, const void* k_pool, const void* v_pool, int64_t num_slots,
+    const int32_t* slot_idx, const int32_t* q_pos, const int32_t* kv_pos,
+    const int32_t* cu_q, const int32_t* cu_kv, int32_t batch,
+    int32_t Tq, int32_t Tkv, int32_t max_q, int32_t max_kv,
+    int32_t Hq, int32_t Hkv, int32_t D, float softmax_scale, int32_t causal,
+    int32_t out_f32, void* O, float* LSE,
+    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Measurement aids (no part of the method): what this GPU sustains on the two
  * resources that bound the path, for the benchmark's "achievable" figures.
  *   esp_probe_mfma_bf16: every wavefront (8 per CU, all CUs) runs `iters` rounds of

@@ -27,7 +27,7 @@ EXPORTS = (
     "esp_partial_attn_prefill_f32", "esp_merge_partials_f32",
     "esp_debug_set_validate", "esp_debug_set_prefill_sync_ticks",
     "esp_partial_attn_decode_static", "esp_partial_attn_prefill_retain", "esp_plan_prefill_batches_monotone",
-    "esp_partial_attn_decode_merge",
+    "esp_partial_attn_decode_merge", "esp_partial_attn_prefill_pool_direct",
 )
 ESP_DECODE_STATIC_SCRATCH_BYTES = 32 << 20
 
@@ -76,6 +76,8 @@ def _load() -> ctypes.CDLL:
     L.esp_kv_gather.restype = i32
     L.esp_partial_attn_prefill_pool.argtypes = [vp, vp, vp, i64] + [vp] * 5 + [i32] * 8 + [f32, i32, vp, vp, vp, sz, vp]
     L.esp_partial_attn_prefill_pool.restype = i32
+    L.esp_partial_attn_prefill_pool_direct.argtypes = [vp, vp, vp, i64] + [vp] * 5 + [i32] * 8 + [f32, i32, i32, vp, vp, vp, sz, vp]
+    L.esp_partial_attn_prefill_pool_direct.restype = i32
     L.esp_prefill_pool_workspace_bytes.argtypes = [i32] * 6
     L.esp_prefill_pool_workspace_bytes.restype = sz
     L.esp_probe_mfma_bf16.argtypes = [vp, i64, i32, vp, vp, vp]
@@ -386,8 +388,18 @@ def esp_prefill_pool_workspace_bytes(Tq, Tkv, batch, Hq, Hkv, D) -> int:
     return int(lib.esp_prefill_pool_workspace_bytes(Tq, Tkv, batch, Hq, Hkv, D))
 
 
+def esp_partial_attn_prefill_pool_direct(q, k_pool, v_pool, slot_idx, q_pos, kv_pos, cu_q=None, cu_kv=None, max_q=None,
+                                         max_kv=None, softmax_scale=None, causal=True, O=None, LSE=None, workspace=None,
+                                         out_dtype=None):
+    """esp_partial_attn_prefill over the shard whose row i is pool row slot_idx[i], the tile transfers reading the pool
+    rows themselves (no staging copy).  O bf16, or fp32 with out_dtype=torch.float32 / an fp32 O.  Returns (O, LSE)."""
+    return esp_partial_attn_prefill_pool(q, k_pool, v_pool, slot_idx, q_pos, kv_pos, cu_q, cu_kv, max_q, max_kv, softmax_scale,
+                                         causal, O, LSE, workspace, _direct=True, _out_dtype=out_dtype)
+
+
 def esp_partial_attn_prefill_pool(q, k_pool, v_pool, slot_idx, q_pos, kv_pos, cu_q=None, cu_kv=None, max_q=None, max_kv=None,
-                                  softmax_scale=None, causal=True, O=None, LSE=None, workspace=None):
+                                  softmax_scale=None, causal=True, O=None, LSE=None, workspace=None, _direct=False,
+                                  _out_dtype=None):
     """esp_partial_attn_prefill over the shard whose row i is pool row slot_idx[i].  Returns (O, LSE)."""
     _dev(q, torch.bfloat16, "q"); _dev(k_pool, torch.bfloat16, "k_pool"); _dev(v_pool, torch.bfloat16, "v_pool")
     _dev(slot_idx, torch.int32, "slot_idx"); _dev(q_pos, torch.int32, "q_pos"); _dev(kv_pos, torch.int32, "kv_pos")
@@ -408,13 +420,27 @@ def esp_partial_attn_prefill_pool(q, k_pool, v_pool, slot_idx, q_pos, kv_pos, cu
         max_q, max_kv = Tq, Tkv
     if softmax_scale is None:
         softmax_scale = D ** -0.5
+    odt = torch.bfloat16
+    if _direct:
+        odt = O.dtype if O is not None else (_out_dtype or torch.bfloat16)
+        if odt not in (torch.bfloat16, torch.float32):
+            raise ValueError("prefill (pool): O must be bf16 or fp32")
     if O is None:
-        O = torch.empty_like(q)
+        O = torch.empty(q.shape, dtype=odt, device=q.device)
     if LSE is None:
         LSE = torch.empty((Tq, Hq), dtype=torch.float32, device=q.device)
-    _dev(O, torch.bfloat16, "O"); _dev(LSE, torch.float32, "LSE")
+    _dev(O, odt, "O"); _dev(LSE, torch.float32, "LSE")
     if O.shape != q.shape or LSE.shape != (Tq, Hq):
         raise ValueError("prefill (pool): output shape mismatch")
+    if _direct:
+        if workspace is None:
+            workspace = _workspace(esp_prefill_workspace_bytes(Tq, Tkv, batch, Hq, Hkv, D), q.device)
+        _check(lib.esp_partial_attn_prefill_pool_direct(_ptr(q), _ptr(k_pool), _ptr(v_pool), S, _ptr(slot_idx), _ptr(q_pos),
+                                                        _ptr(kv_pos), _ptr(cu_q), _ptr(cu_kv), batch, Tq, Tkv, int(max_q), int(max_kv),
+                                                        Hq, Hkv, D, float(softmax_scale), 1 if causal else 0,
+                                                        1 if odt == torch.float32 else 0, _ptr(O), _ptr(LSE), _ptr(workspace),
+                                                        workspace.numel(), _stream()))
+        return O, LSE
     if workspace is None:
         workspace = _workspace(esp_prefill_pool_workspace_bytes(Tq, Tkv, batch, Hq, Hkv, D), q.device)
     _check(lib.esp_partial_attn_prefill_pool(_ptr(q), _ptr(k_pool), _ptr(v_pool), S, _ptr(slot_idx), _ptr(q_pos), _ptr(kv_pos),

@@ -105,7 +105,7 @@ static esp_status prefill_entry(const void* q, const void* k, const void* v, con
                                 int32_t D, float softmax_scale, int32_t causal, int32_t o_f32, void* O, float* LSE,
                                 void* workspace, size_t workspace_bytes, void* stream,
                                 const int32_t* retain_slot = nullptr, void* k_pool = nullptr, void* v_pool = nullptr,
-                                int64_t num_slots = 0) {
+                                int64_t num_slots = 0, const int32_t* kv_slot = nullptr) {
     if (Tq < 0 || Tkv < 0 || batch < 1 || max_q < 0 || max_kv < 0)
         return fail(ESP_ERR_INVALID_ARG, "prefill: negative size or batch < 1");
     if (!heads_ok(Hq, Hkv)) return fail(ESP_ERR_INVALID_ARG, "prefill: Hq=%d must be a positive multiple of Hkv=%d", Hq, Hkv);
@@ -125,6 +125,10 @@ static esp_status prefill_entry(const void* q, const void* k, const void* v, con
         if (Tq == 0) return launch_kv_append(k, v, retain_slot, Tkv, k_pool, v_pool, Hkv * D * 2, (hipStream_t)stream);
     }
     if (Tq == 0) return ESP_OK;
+    if (kv_slot && Tkv > 0 && debug_validate()) {                   // k and v are the pools: rows come from these slots
+        esp_status st = check_slots("prefill (pool)", kv_slot, Tkv, num_slots, false, false, (hipStream_t)stream);
+        if (st != ESP_OK) return st;
+    }
     if (!q || !O || !LSE || !q_pos) return fail(ESP_ERR_INVALID_ARG, "prefill: null q/q_pos/O/LSE");
     if (Tkv > 0 && (!k || !v || !kv_pos)) return fail(ESP_ERR_INVALID_ARG, "prefill: null k/v/kv_pos");
     if (!(softmax_scale == softmax_scale) || softmax_scale < 0.f) return fail(ESP_ERR_INVALID_ARG, "prefill: bad softmax_scale");
@@ -139,7 +143,7 @@ static esp_status prefill_entry(const void* q, const void* k, const void* v, con
     }
     return launch_prefill(q, k, v, q_pos, kv_pos, cu_q, cu_kv, batch, Tq, Tkv, max_q, max_kv, Hq, Hkv,
                           softmax_scale, causal, o_f32, O, LSE, workspace, workspace_bytes,
-                          Tkv > 0 ? retain_slot : nullptr, k_pool, v_pool, (hipStream_t)stream);
+                          Tkv > 0 ? retain_slot : nullptr, k_pool, v_pool, Tkv > 0 ? kv_slot : nullptr, (hipStream_t)stream);
 }
 
 esp_status esp_partial_attn_prefill_retain(const void* q, const void* k, const void* v, const int32_t* q_pos,
@@ -225,6 +229,20 @@ esp_status esp_partial_attn_prefill_pool(const void* q, const void* k_pool, cons
     if (st != ESP_OK) return st;
     return esp_partial_attn_prefill(q, ws, ws + stage, q_pos, kv_pos, cu_q, cu_kv, batch, Tq, Tkv, max_q, max_kv, Hq, Hkv, D,
                                     softmax_scale, causal, O, LSE, ws + 2 * stage, workspace_bytes - 2 * stage, stream);
+}
+
+esp_status esp_partial_attn_prefill_pool_direct(const void* q, const void* k_pool, const void* v_pool, int64_t num_slots,
+                                                const int32_t* slot_idx, const int32_t* q_pos, const int32_t* kv_pos,
+                                                const int32_t* cu_q, const int32_t* cu_kv, int32_t batch, int32_t Tq,
+                                                int32_t Tkv, int32_t max_q, int32_t max_kv, int32_t Hq, int32_t Hkv, int32_t D,
+                                                float softmax_scale, int32_t causal, int32_t out_f32, void* O, float* LSE,
+                                                void* workspace, size_t workspace_bytes, void* stream) {
+    if (Tkv < 0 || num_slots < 0) return fail(ESP_ERR_INVALID_ARG, "prefill (pool): negative size");
+    if (Tkv > 0 && !slot_idx) return fail(ESP_ERR_INVALID_ARG, "prefill (pool): null slot_idx");
+    if (Tkv > 0 && num_slots == 0) return fail(ESP_ERR_INVALID_ARG, "prefill (pool): empty pool");
+    return prefill_entry(q, k_pool, v_pool, q_pos, kv_pos, cu_q, cu_kv, batch, Tq, Tkv, max_q, max_kv, Hq, Hkv, D, softmax_scale,
+                         causal, out_f32 ? 1 : 0, O, LSE, workspace, workspace_bytes, stream, nullptr, nullptr, nullptr, num_slots,
+                         slot_idx);
 }
 
 // argument checks common to the two decode entry points; *done is set when there is nothing to launch

@@ -66,6 +66,7 @@ esp_status launch_prefill(const void* q, const void* k, const void* v, const int
                           const int32_t* cu_q, const int32_t* cu_kv, int32_t batch, int32_t Tq, int32_t Tkv,
                           int32_t max_q, int32_t max_kv, int32_t Hq, int32_t Hkv, float softmax_scale,
                           int32_t causal, int32_t o_f32, void* O, float* LSE, void* workspace, size_t workspace_bytes,
-                          const int32_t* retain_slot, void* k_pool, void* v_pool, hipStream_t stream);
+                          const int32_t* retain_slot, void* k_pool, void* v_pool, const int32_t* kv_slot,
+                          hipStream_t stream);
 
 }  // namespace esp

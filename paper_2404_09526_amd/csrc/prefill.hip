@@ -93,6 +93,7 @@ struct PrefillArgs {
     const uint16_t* q; const uint16_t* k; const uint16_t* v;
     const int32_t* q_pos; const int32_t* kv_pos; const int32_t* cu_q; const int32_t* cu_kv;
     const int32_t* retain_slot;       // [Tkv] pool slot of every shard row (negative: not kept), or null: nothing is kept
+    const int32_t* kv_slot;           // [Tkv] pool slot of every shard row when k and v ARE the token pools; null: dense shard
     uint16_t* k_pool; uint16_t* v_pool;
     void* O; float* LSE;              // O: bf16 [Tq, Hq, 128], or fp32 of the same shape when o_f32 is set
     int32_t batch, Tq, Tkv, Hq, Hkv, causal, o_f32;
@@ -138,6 +139,11 @@ __device__ __forceinline__ void load_to_lds_b128(uint32_t lds_addr, const void* 
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :: "s"(lds_addr), "v"(voff), "s"(gbase) : "memory", "m0");
 }
+// the same with a full address per lane (rows scattered over a pool larger than a 32-bit offset reaches)
+__device__ __forceinline__ void load_to_lds_b128_at(uint32_t lds_addr, const void* src) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(lds_addr), "v"(src) : "memory", "m0");
+}
 __device__ __forceinline__ void load_to_lds_b32(uint32_t lds_addr, const void* gbase, uint32_t voff) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
                  :: "s"(lds_addr), "v"(voff), "s"(gbase) : "memory", "m0");
@@ -163,14 +169,20 @@ template <int V> struct IC { static constexpr int value = V; };
 // stay in LDS, after the sweep; an earlier tile j at the top of iteration j: complete in LDS by then, and issued
 // ahead of the iteration's transfers, so that the hand-counted waits still see those as the newest operations in
 // flight (they have to sit out the stores, though, which is why the tiles at the end are left for later).
-template <bool RETAIN>
+//
+// POOL (MODE 2): the shard's rows live in the token pool (a.k / a.v are the pools, a.kv_slot the slot of every shard
+// row, Sec. 4.1 / 4.2: KV that an instance kept stays where it was placed).  The tile transfers take each row from its
+// slot: the slots of tile t travel to a ring of 4 LDS stages (stage t % 4) one iteration before the tile's first
+// transfer is issued, every lane reads the slot of the row its 16 bytes belong to and forms the address itself.
+template <int MODE>
 __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
+    constexpr bool RETAIN = MODE == 1, POOL = MODE == 2;
     // One LDS block, V stages first: an LDS instruction adds a 16-bit immediate to its address register, so with
     // each array's base folded into the per-lane register every operand read of the loop needs no address math.
     constexpr int kLdsV = 0, kLdsK = kLdsV + kStages * kTileBytes, kLdsPos = kLdsK + kStages * kKTileBytes,
                   kLdsQmm = kLdsPos + kStages * kBN * 4, kLdsSched = kLdsQmm + 2 * kPfWaves * 4,
                   kLdsFlag = kLdsSched + kPfWaves * 64 * 8, kLdsSlot = kLdsFlag + 16,
-                  kLdsTotal = kLdsSlot + (RETAIN ? 8 * kBN * 4 : 0);
+                  kLdsTotal = kLdsSlot + (RETAIN ? 8 * kBN * 4 : POOL ? kStages * kBN * 4 : 0);
     __shared__ __attribute__((aligned(1024))) unsigned char smem[kLdsTotal];
     unsigned char (*lds_k)[kKTileBytes] = (unsigned char (*)[kKTileBytes])(smem + kLdsK);
     unsigned char (*lds_v)[kTileBytes] = (unsigned char (*)[kTileBytes])(smem + kLdsV);
@@ -272,10 +284,41 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     };
     const uint32_t gv0 = v_goff(st_r0, st_r0), gv1 = v_goff(st_r1, st_r1);
     const uint32_t gk0 = k_goff(wave, kBN - 1), gk1 = k_goff(wave + 8, kBN - 1), gk2 = k_goff(16, kBN - 1);
-    const char* kreq = (const char*)a.k + ((int64_t)kv_lo * a.Hkv + kvh) * (kHeadDim * 2);   // row kv_lo, head kvh
-    const char* vreq = (const char*)a.v + ((int64_t)kv_lo * a.Hkv + kvh) * (kHeadDim * 2);
+    const uint32_t lds_base0 = (uint32_t)(uintptr_t)(ESP_LDS unsigned char*)smem;
+    // row kv_lo, head kvh (POOL: slot 0, head kvh)
+    const char* kreq = (const char*)a.k + ((int64_t)(POOL ? 0 : kv_lo) * a.Hkv + kvh) * (kHeadDim * 2);
+    const char* vreq = (const char*)a.v + ((int64_t)(POOL ? 0 : kv_lo) * a.Hkv + kvh) * (kHeadDim * 2);
+    // POOL: per transfer of this lane, the tile row its 16 bytes belong to (times 4: byte offset into a ring stage,
+    // low byte) and where in the row's 256 bytes they sit (from bit 8 up)
+    auto pool_key = [&](int row, int within) { return (uint32_t)((within << 8) | (row << 2)); };
+    auto k_key = [&](int n) {
+        const int B = 1024 * n + 16 * lane, row = B / kKRow, within = B - row * kKRow;
+        return pool_key(min(row, kBN - 1), within < 256 ? within : 0);
+    };
+    const uint32_t pk0 = POOL ? k_key(wave) : 0, pk1 = POOL ? k_key(wave + 8) : 0, pk2 = POOL ? k_key(16) : 0;
+    const uint32_t pv0 = POOL ? pool_key(st_r0, (st_p ^ ((st_r0 & 3) << 2)) << 4) : 0;
+    const uint32_t pv1 = POOL ? pool_key(st_r1, (st_p ^ ((st_r1 & 3) << 2)) << 4) : 0;
+    // the row's address: its slot from ring stage st, one 32 x 32 -> 64-bit multiply-add
+    auto pool_slot = [&](int st, uint32_t key) { return *(const int32_t*)(smem + kLdsSlot + st * (kBN * 4) + (key & 0xff)); };
+    auto pool_at = [&](const char* base, int32_t slot, uint32_t key) {
+        return base + ((uint64_t)(uint32_t)slot * kv_row_bytes + (key >> 8));
+    };
+    auto pool_src = [&](const char* base, int st, uint32_t key) { return pool_at(base, pool_slot(st, key), key); };
+    // slots of tile t into ring stage st (wavefront 6); rows past the end of a ragged last tile repeat the last row's
+    // slot, so their transfers re-read that row (their scores get masked)
+    const int32_t* slot_req = POOL ? a.kv_slot + kv_lo : nullptr;
+    auto fetch_pool_slots = [&](int t, int st) {
+        if (!POOL || wave != 6 || t >= nkt) return;
+        const int rows = min(kBN, kv_len - t * kBN);
+        load_to_lds_b32(lds_base0 + kLdsSlot + st * (kBN * 4), slot_req + t * kBN, min(lane, rows - 1) * 4);
+    };
+    // the same inside the sweep's plain iterations, where the tile is a full one that exists: nothing to work out
+    const uint32_t lane4 = lane * 4;
+    auto fetch_pool_slots_full = [&](int t, int st) {
+        load_to_lds_b32(lds_base0 + kLdsSlot + st * (kBN * 4), slot_req + t * kBN, lane4);
+    };
     const int32_t* preq = a.kv_pos + kv_lo;
-    const uint32_t lds_base = (uint32_t)(uintptr_t)(ESP_LDS unsigned char*)smem;
+    const uint32_t lds_base = lds_base0;
     const uint32_t lds_k0 = lds_base + kLdsK, lds_v0 = lds_base + kLdsV, lds_p0 = lds_base + kLdsPos;
 
     // K tile at kt into K stage st: 2 transfers per wavefront, 3 for wavefront 7; `part` picks one of them, so that
@@ -286,6 +329,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         const uint32_t ko = lds_k0 + st * kKTileBytes;
         const int n = part == 0 ? wave : part == 1 ? wave + 8 : 16;
         if (part == 2 && wave != 7) return;
+        if constexpr (POOL) { load_to_lds_b128_at(ko + 1024 * n, pool_src(kreq, st, part == 0 ? pk0 : part == 1 ? pk1 : pk2)); return; }
         if (__builtin_expect(tail, 0)) load_to_lds_b128(ko + 1024 * n, kt, k_goff(n, tail_rows - 1));
         else load_to_lds_b128(ko + 1024 * n, kt, part == 0 ? gk0 : part == 1 ? gk1 : gk2);
     };
@@ -296,6 +340,8 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         if (part == 2) {
             if (wave != 0) return;
             load_to_lds_b32(lds_p0 + st * (kBN * 4), pt, (tail ? min(lane, last) : lane) * 4);
+        } else if constexpr (POOL) {
+            load_to_lds_b128_at(vo + 1024 * part, pool_src(vreq, st, part == 0 ? pv0 : pv1));
         } else if (__builtin_expect(tail, 0)) {
             const int r = part == 0 ? st_r0 : st_r1;
             load_to_lds_b128(vo + 1024 * part, vt, v_goff(r, min(r, last)));
@@ -372,6 +418,12 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
 
     // the first tiles are requested right away, so that their latency hides behind the Q load and the schedule
     // scan (tiles the scan later finds hidden are fetched for nothing, which is harmless: they exist)
+    if constexpr (POOL) {
+        // the first four tiles' slots must be in LDS, and visible to every wavefront, before the first transfer
+        fetch_pool_slots(0, 0); fetch_pool_slots(1, 1); fetch_pool_slots(2, 2); fetch_pool_slots(3, 3);
+        wait_vm<0>();
+        wg_barrier();
+    }
     if (nkt > 4) {                                                   // the usual case, without a conditional in it
         fetch_k(kreq, 0, false); fetch_v(vreq, preq, 0, false);
         fetch_k(kreq + tile_bytes, 1, false); fetch_v(vreq + tile_bytes, preq + kBN, 1, false);
@@ -455,6 +507,9 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     int2* lds_mm = (int2*)(smem + kLdsSched);
     if (a.causal) lds_mm[tid] = mm_first;
     wg_barrier();          // LDS only: the Q loads and tile transfers stay in flight
+    // (POOL: every wavefront has issued its first transfers, i.e. read the slots of tile 0: those of tile 4, which
+    // iteration 0 asks for, may replace them; they land before the wait that ends the prologue)
+    fetch_pool_slots(4, 0);
     if (a.causal) {
         int wg_qmax = lds_qmm[1][0];
 #pragma unroll
@@ -648,6 +703,9 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     // iteration j-1, and V(j+2) over V(j-2), last read in the first steps of iteration j-1: both before the
     // barrier that ended iteration j-1.  What a wavefront fetched in iteration j-1 has landed before the barrier
     // that ends its iteration j, and is first read in iteration j+1.
+    // POOL, plain iterations: wavefront 6 fetches the slots of tile j+5 while j is below this (the sweep reaches that
+    // tile, and it is a full one: see n_plain); no other wavefront does
+    const int plain_slots = POOL && wave == 6 ? n_vis - 5 : INT_MIN;
     auto iteration = [&](auto st_c, auto par_c, auto plain_c, int j) {
         constexpr int ST = decltype(st_c)::value, PAR = decltype(par_c)::value;
         constexpr bool PLAIN = decltype(plain_c)::value != 0;
@@ -661,6 +719,14 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
         for (int m = 0; m < 16; ++m) {
             const int t = m >> 1, kvb = m & 1;
+            // POOL: the slot of this step's transfer is read first, ahead of the step's fragment reads: LDS answers in
+            // order, so a read placed next to the transfer would wait for those as well
+            int32_t pslot = 0;
+            if constexpr (POOL) {
+                if (m == 1 && do_k && wave == 7) pslot = pool_slot(ST, pk2);
+                if ((m == 3 || m == 6) && do_k) pslot = pool_slot(ST, m == 3 ? pk0 : pk1);
+                if ((m == 9 || m == 12) && do_v) pslot = pool_slot(ST2, m == 9 ? pv0 : pv1);
+            }
             if (t == 0) {                                 // S^T of tile j+1 (after the last tile: stale data, unused)
                 floatx16 zero;
 #pragma unroll
@@ -680,13 +746,31 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
             pair_sum_pack(m, !PLAIN);
             // the transfers of this iteration, spread out (a burst from all wavefronts at once backs up the memory
             // pipeline); the odd ones of wavefronts 7 and 0 go first, so that "all but the last four have landed"
-            // is the same wait for every wavefront
+            // is the same wait for every wavefront.  (Issued last instead, with a wait count per wavefront, they
+            // would have a whole iteration more to land; measured, that is slower: 1.6 % on the 8K x 8K causal
+            // shard, 6 % on a chunk against a 256K prefix.)
             if (m == 1) {
-                if (do_k) { if (!PLAIN && j >= own_lo) fetch_slots(j + 4); fetch_k_part(k_next, ST, tail_k, 2); }
+                if constexpr (POOL) {                   // over tile j+1's slots, last read in iteration j-1
+                    if (PLAIN) { if (j < plain_slots) fetch_pool_slots_full(j + 5, ST1); }
+                    else if (j + 5 < n_vis) fetch_pool_slots(j + 5, ST1);
+                }
+                if (KEEP && !PLAIN && do_k && j >= own_lo) fetch_slots(j + 4);
+                if constexpr (POOL) {
+                    if (do_k && wave == 7) load_to_lds_b128_at(lds_k0 + ST * kKTileBytes + 1024 * 16, pool_at(kreq, pslot, pk2));
+                } else if (do_k) {
+                    fetch_k_part(k_next, ST, tail_k, 2);
+                }
                 if (do_v) fetch_v_part(v_next, p_next, ST2, tail_v, 2);
             }
-            if (do_k && (m == 3 || m == 6)) fetch_k_part(k_next, ST, tail_k, m / 6);
-            if (do_v && (m == 9 || m == 12)) fetch_v_part(v_next, p_next, ST2, tail_v, m / 12);
+            if constexpr (POOL) {
+                if (do_k && (m == 3 || m == 6))
+                    load_to_lds_b128_at(lds_k0 + ST * kKTileBytes + 1024 * (m == 3 ? wave : wave + 8), pool_at(kreq, pslot, m == 3 ? pk0 : pk1));
+                if (do_v && (m == 9 || m == 12))
+                    load_to_lds_b128_at(lds_v0 + ST2 * kTileBytes + wave * 2048 + 1024 * (m / 12), pool_at(vreq, pslot, m == 9 ? pv0 : pv1));
+            } else {
+                if (do_k && (m == 3 || m == 6)) fetch_k_part(k_next, ST, tail_k, m / 6);
+                if (do_v && (m == 9 || m == 12)) fetch_v_part(v_next, p_next, ST2, tail_v, m / 12);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
         close_tile(sc, !PLAIN);
@@ -738,7 +822,8 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
     //   2. general iterations for the rest, again in groups of four, then one by one.
     //      (an owner: also short of its first owned tile, unless that is one of the sweep's last four, which are
     //      stored after the sweep)
-    const int n_plain = max(0, min(min(min(min(n_vis - 4, n_need), mask_from), ragged_tile >= 0 ? nkt - 5 : INT_MAX),
+    //      (POOL: one tile earlier before a ragged last tile, whose slot list a plain iteration does not fetch)
+    const int n_plain = max(0, min(min(min(min(n_vis - 4, n_need), mask_from), ragged_tile >= 0 ? nkt - 5 - (POOL ? 1 : 0) : INT_MAX),
                                    KEEP && own_lo < n_vis - 4 ? own_lo : INT_MAX)) & ~3;
     int j = 0;
     for (; j < n_plain; j += 4) {
@@ -775,6 +860,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
         const bool tail_k = jj + 4 == ragged_tile, tail_v = jj + 2 == ragged_tile;
         if (KEEP && jj < n_vis - 4) keep_tile(jj, jj & 3);
         if (do_k && jj >= own_lo) fetch_slots(jj + 4);
+        if (POOL && jj + 5 < n_vis) fetch_pool_slots(jj + 5, (jj + 1) & 3);
         if (do_k) fetch_k_part(k_next, jj & 3, tail_k, 2);
         if (do_v) fetch_v_part(v_next, p_next, (jj + 2) & 3, tail_v, 2);
         if (do_k) { fetch_k_part(k_next, jj & 3, tail_k, 0); fetch_k_part(k_next, jj & 3, tail_k, 1); }
@@ -818,6 +904,11 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
             for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
         for (int t = 0; t < n_vis; ++t) {
             wg_barrier();
+            if constexpr (POOL) {
+                fetch_pool_slots(t, 0);
+                wait_vm<0>();
+                wg_barrier();
+            }
             fetch_k(kreq + (int64_t)t * tile_bytes, 0, t == ragged_tile);
             fetch_v(vreq + (int64_t)t * tile_bytes, preq + t * kBN, 0, t == ragged_tile);
             wait_vm<0>();
@@ -1032,12 +1123,14 @@ esp_status launch_prefill(const void* q, const void* k, const void* v, const int
                           const int32_t* cu_q, const int32_t* cu_kv, int32_t batch, int32_t Tq, int32_t Tkv,
                           int32_t max_q, int32_t max_kv, int32_t Hq, int32_t Hkv, float softmax_scale,
                           int32_t causal, int32_t o_f32, void* O, float* LSE, void* workspace, size_t workspace_bytes,
-                          const int32_t* retain_slot, void* k_pool, void* v_pool, hipStream_t stream) {
+                          const int32_t* retain_slot, void* k_pool, void* v_pool, const int32_t* kv_slot,
+                          hipStream_t stream) {
     (void)max_q; (void)max_kv;
     PrefillArgs a;
     a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
     a.q_pos = q_pos; a.kv_pos = kv_pos; a.cu_q = cu_q; a.cu_kv = cu_kv;
     a.O = O; a.LSE = LSE; a.o_f32 = o_f32 ? 1 : 0;
+    a.kv_slot = kv_slot;
     a.retain_slot = retain_slot; a.k_pool = (uint16_t*)k_pool; a.v_pool = (uint16_t*)v_pool;
     a.batch = batch; a.Tq = Tq; a.Tkv = Tkv; a.Hq = Hq; a.Hkv = Hkv; a.causal = causal ? 1 : 0;
     a.scale_log2 = softmax_scale * kLog2e;
@@ -1059,10 +1152,13 @@ esp_status launch_prefill(const void* q, const void* k, const void* v, const int
                     (cus / 8) % a.heads_per_xcd == 0 &&
                     8 * (2 + 16 * (size_t)a.heads_per_xcd) <= workspace_bytes) ? 1 : 0;
     a.sync_ticks = g_sync_ticks.load(std::memory_order_relaxed);
-    if (retain_slot)
-        hipLaunchKernelGGL(prefill_kernel<true>, dim3(grid), dim3(kPfWaves * 64), 0, stream, a);
+    if (kv_slot && retain_slot) return fail(ESP_ERR_INVALID_ARG, "prefill: rows that are read from the pool are in it already");
+    if (kv_slot)
+        hipLaunchKernelGGL(prefill_kernel<2>, dim3(grid), dim3(kPfWaves * 64), 0, stream, a);
+    else if (retain_slot)
+        hipLaunchKernelGGL(prefill_kernel<1>, dim3(grid), dim3(kPfWaves * 64), 0, stream, a);
     else
-        hipLaunchKernelGGL(prefill_kernel<false>, dim3(grid), dim3(kPfWaves * 64), 0, stream, a);
+        hipLaunchKernelGGL(prefill_kernel<0>, dim3(grid), dim3(kPfWaves * 64), 0, stream, a);
     return check_launch("prefill_kernel");
 }
 

@@ -24,6 +24,12 @@ def say(msg):
     print(f"[case] {msg}", flush=True)
 
 
+def seeded_positions(n, hi, seed, device):
+    """n query positions drawn uniformly from [0, hi), the same in every run."""
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    return torch.randint(0, hi, (n,), generator=g, dtype=torch.int32).to(device)
+
+
 def run_prefill_case(esp, pc, check_merged=True, workspace=None):
     """Runs every shard through the HIP path, with bf16 and with fp32 partial outputs, and checks each partial.  With
     several shards: the fp32 partials are merged and compared with the oracle's merge of ITS OWN fp64 partials, i.e.
@@ -502,7 +508,7 @@ def test_prefill_more_items_than_workgroups(esp, cuda, Hq, Hkv):
     Short KV keeps the oracle cheap; every query row is checked."""
     Tq = 256 * 72 + 40                                  # 73 query tiles (the last one ragged) x Hq heads > 256 items
     pc = wl.contiguous_prefill(f"many-items-{Hq}/{Hkv}", Tq, 200, [(0, 330), (330, 700)], Hq, Hkv, 51, cuda)
-    pc.q_pos[:] = torch.randint(0, 900, (Tq,), dtype=torch.int32, device=cuda)       # every tile sees a different part
+    pc.q_pos[:] = seeded_positions(Tq, 900, 901, cuda)       # every tile sees a different part
     run_prefill_case(esp, pc)
 
 
@@ -620,6 +626,103 @@ def test_prefill_over_pool_resident_rows(esp, cuda, layout):
         check_o_lse(O.float().cpu().numpy().reshape(-1, D), LSE.cpu().numpy().reshape(-1), Or, Lr, f"{pc.name} shard {si}")
 
 
+def run_pool_direct_case(esp, pc, seed, spare_slots=777):
+    """Every shard of the case is laid out in a pool at random distinct slots (noise everywhere else) and attended by
+    the call whose tile transfers read the pool rows themselves; bf16 and fp32 output, every query row against the
+    oracle on ITS OWN gathered rows; and bit for bit against the dense call on the same rows (same tiles, same order
+    of operations: only where a row comes from differs)."""
+    rng = np.random.default_rng(seed)
+    qb, qp = wl.bits(pc.q), wl.host_i32(pc.q_pos)
+    cu_q = wl.host_i32(pc.cu_q)
+    Tq, Hq, D = pc.q.shape
+    rows = np.repeat(np.arange(Tq, dtype=np.int64), Hq); heads = np.tile(np.arange(Hq, dtype=np.int64), Tq)
+    req_of_row = np.searchsorted(cu_q, np.arange(Tq), side="right") - 1
+    single = pc.batch == 1
+    to = lambda a: torch.from_numpy(a.view(np.int16)).to(pc.q.device).view(torch.bfloat16)
+    for si, s in enumerate(pc.shards):
+        S = 2 * s.k.shape[0] + spare_slots
+        kp, vp, slots = pool_image(rng, s, S)
+        say(f"{pc.name} shard {si} from the pool: Tq={Tq} Tkv={len(slots)} pool={S} Hq={Hq} Hkv={pc.Hkv} batch={pc.batch} causal={pc.causal}")
+        args = (pc.q, to(kp), to(vp), torch.from_numpy(slots).to(pc.q.device), pc.q_pos, s.kv_pos,
+                None if single else pc.cu_q, None if single else s.cu_kv, None if single else pc.max_q, None if single else s.max_kv)
+        O = torch.full_like(pc.q, float("nan")); LSE = torch.full((Tq, Hq), float("nan"), dtype=torch.float32, device=pc.q.device)
+        esp.esp_partial_attn_prefill_pool_direct(*args, softmax_scale=pc.scale, causal=pc.causal, O=O, LSE=LSE)
+        O32 = torch.full(pc.q.shape, float("nan"), dtype=torch.float32, device=pc.q.device); LSE32 = torch.full_like(LSE, float("nan"))
+        esp.esp_partial_attn_prefill_pool_direct(*args, softmax_scale=pc.scale, causal=pc.causal, O=O32, LSE=LSE32)
+        Od, Ld = esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos, *args[6:], softmax_scale=pc.scale, causal=pc.causal)
+        torch.cuda.synchronize()
+        if Tq > 0:
+            kg, vg = oracle.kv_gather(kp, vp, slots)
+            assert np.array_equal(kg, wl.bits(s.k)) and np.array_equal(vg, wl.bits(s.v))
+            cu_kv = wl.host_i32(s.cu_kv)
+            lo, hi = cu_kv[req_of_row[rows]], cu_kv[req_of_row[rows] + 1]
+            Or, Lr = oracle.partial_attn(qb, kg, vg, qp, wl.host_i32(s.kv_pos), pc.scale, pc.causal, rows, heads, lo, hi)
+            check_o_lse(O.float().cpu().numpy().reshape(-1, D), LSE.cpu().numpy().reshape(-1), Or, Lr, f"{pc.name} shard {si} from the pool")
+            check_o_lse(O32.cpu().numpy().reshape(-1, D), LSE32.cpu().numpy().reshape(-1), Or, Lr, f"{pc.name} shard {si} from the pool (fp32 out)")
+        assert torch.equal(O.view(torch.int16), Od.view(torch.int16)) and torch.equal(LSE.view(torch.int32), Ld.view(torch.int32))
+        assert torch.equal(O32.to(torch.bfloat16).view(torch.int16), O.view(torch.int16)) and torch.equal(LSE32.view(torch.int32), LSE.view(torch.int32))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("layout", ["one-request", "var-len-gqa"])
+def test_prefill_reading_pool_rows_in_the_tile_transfers(esp, cuda, layout):
+    if layout == "one-request":
+        run_pool_direct_case(esp, wl.contiguous_prefill("pool-direct-1req", 300, 400, [(0, 700)], 4, 4, 61, cuda), 141)
+    else:
+        run_pool_direct_case(esp, wl.striped_prefill("pool-direct-varlen", [70, 257, 130, 1, 64], 2, 1, 8, 2, 62, cuda), 142)
+
+
+@pytest.mark.gpu
+def test_prefill_from_pool_long_shard_ragged_tail_and_short_shards(esp, cuda):
+    """Many tiles (the slot ring wraps many times; plain and masked iterations; tiles that only some wavefronts see),
+    a ragged last tile, and shards of 1 .. 5 tiles (every branch of the start-up with few tiles)."""
+    run_pool_direct_case(esp, wl.contiguous_prefill("pool-direct-long", 700, 3000, [(0, 3700 - 29)], 4, 2, 63, cuda), 143)
+    for n in (1, 63, 64, 65, 128, 200, 256, 257, 320):
+        run_pool_direct_case(esp, wl.contiguous_prefill(f"pool-direct-{n}", 130, 400, [(0, n)], 2, 2, 64 + n, cuda), 144 + n, spare_slots=50)
+
+
+@pytest.mark.gpu
+def test_prefill_from_pool_non_causal_unsorted_and_hidden_shards(esp, cuda):
+    run_pool_direct_case(esp, wl.contiguous_prefill("pool-direct-noncausal", 100, 0, [(0, 1000)], 4, 4, 65, cuda, causal=False), 151)
+    pc = wl.contiguous_prefill("pool-direct-unsorted", 200, 500, [(0, 900)], 4, 4, 66, cuda)
+    g = torch.Generator(device="cpu").manual_seed(66)
+    pc.q_pos[:] = torch.randint(0, 1500, (200,), generator=g, dtype=torch.int32).to(cuda)
+    pc.shards[0].kv_pos[:] = torch.randint(0, 1500, (900,), generator=g, dtype=torch.int32).to(cuda)
+    run_pool_direct_case(esp, pc, 152)
+    # a shard that lies entirely after the queries: nothing visible, no tile is swept
+    run_pool_direct_case(esp, wl.contiguous_prefill("pool-direct-future", 100, 0, [(5000, 5600)], 4, 4, 67, cuda), 153)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("causal", [False, True])
+def test_prefill_from_pool_exact_sweep(esp, cuda, causal):
+    """The rows' scores leave the range of the optimistic pass: the plain re-sweep also has to find its rows by slot."""
+    Tq, Tkv = 300, 1000
+    pc = wl.contiguous_prefill("pool-direct-overflow", Tq, 1000, [(0, Tkv)], 4, 2, 41, cuda, causal=causal)
+    s = pc.shards[0]
+    u = torch.ones(pc.D, dtype=torch.bfloat16, device=cuda)
+    pc.q[:] = (pc.q.float() * 0.05 + 1.5).to(torch.bfloat16)
+    s.k[:] = (s.k.float() * 0.05).to(torch.bfloat16)
+    s.k[777] = 16.0 * u
+    s.k[990] = 15.5 * u
+    run_pool_direct_case(esp, pc, 154)
+
+
+@pytest.mark.gpu
+def test_prefill_from_pool_more_items_than_workgroups_and_empty_shard(esp, cuda):
+    Tq = 256 * 40 + 7
+    pc = wl.contiguous_prefill("pool-direct-many-items", Tq, 150, [(0, 400)], 8, 8, 68, cuda)
+    pc.q_pos[:] = seeded_positions(Tq, 800, 902, cuda)
+    run_pool_direct_case(esp, pc, 155)
+    # no shard rows at all: O = 0, LSE = -inf, no slot is read
+    q = wl.randn_bf16((70, 4, 128), torch.Generator(device=cuda).manual_seed(3), cuda)
+    pool = torch.zeros((16, 2, 128), dtype=torch.bfloat16, device=cuda)
+    none = torch.zeros(0, dtype=torch.int32, device=cuda)
+    O, LSE = esp.esp_partial_attn_prefill_pool_direct(q, pool, pool, none, torch.arange(70, dtype=torch.int32, device=cuda), none)
+    torch.cuda.synchronize()
+    assert torch.isneginf(LSE).all() and (O == 0).all()
+
+
 @pytest.mark.gpu
 @pytest.mark.parametrize("fill", ["zeros", "ones", "random"])
 def test_prefill_workspace_contents_do_not_matter(esp, cuda, fill):
@@ -628,7 +731,7 @@ def test_prefill_workspace_contents_do_not_matter(esp, cuda, fill):
     worked on exactly once.  More items than workgroups, so that the pool is in use; every query row is checked."""
     Tq = 256 * 40 + 7
     pc = wl.contiguous_prefill(f"workspace-{fill}", Tq, 150, [(0, 400), (400, 650)], 8, 8, 77, cuda)
-    pc.q_pos[:] = torch.randint(0, 800, (Tq,), dtype=torch.int32, device=cuda)
+    pc.q_pos[:] = seeded_positions(Tq, 800, 903, cuda)
     nbytes = esp.esp_prefill_workspace_bytes(Tq, 400, 1, 8, 8, 128)
     if fill == "zeros":
         ws = torch.zeros(nbytes, dtype=torch.uint8, device=cuda)
@@ -647,7 +750,7 @@ def test_prefill_calls_on_two_streams_with_a_workspace_each(esp, cuda):
     cases = []
     for k, (Tq, Hq, Hkv) in enumerate([(256 * 40 + 7, 8, 8), (256 * 36 + 100, 16, 8)]):
         pc = wl.contiguous_prefill(f"two-streams-{k}", Tq, 150, [(0, 400)], Hq, Hkv, 81 + k, cuda)
-        pc.q_pos[:] = torch.randint(0, 800, (Tq,), dtype=torch.int32, device=cuda)
+        pc.q_pos[:] = seeded_positions(Tq, 800, 904, cuda)
         s = pc.shards[0]
         O_ref, L_ref = esp.esp_partial_attn_prefill(pc.q, s.k, s.v, pc.q_pos, s.kv_pos, softmax_scale=pc.scale)
         ws = torch.empty(esp.esp_prefill_workspace_bytes(Tq, 400, 1, Hq, Hkv, 128), dtype=torch.uint8, device=cuda)
@@ -674,7 +777,7 @@ def test_prefill_replayed_from_a_captured_graph(esp, cuda):
     other tests check against the oracle).  More items than workgroups, so that the item pool is in use."""
     Tq = 256 * 40 + 7
     pc = wl.contiguous_prefill("graph-replay", Tq, 150, [(0, 400)], 8, 8, 78, cuda)
-    pc.q_pos[:] = torch.randint(0, 800, (Tq,), dtype=torch.int32, device=cuda)
+    pc.q_pos[:] = seeded_positions(Tq, 800, 905, cuda)
     s = pc.shards[0]
     ws = torch.empty(esp.esp_prefill_workspace_bytes(Tq, 400, 1, 8, 8, 128), dtype=torch.uint8, device=cuda)
     nan_like = lambda t: torch.full_like(t, float("nan"))
@@ -808,7 +911,7 @@ def test_retain_non_causal_and_unsorted(esp, cuda):
 def test_retain_more_items_than_workgroups(esp, cuda, Hq, Hkv):
     Tq = 256 * 72 + 40
     pc = wl.contiguous_prefill(f"retain-many-items-{Hq}/{Hkv}", Tq, 200, [(0, 330), (330, 700)], Hq, Hkv, 125, cuda)
-    pc.q_pos[:] = torch.randint(0, 900, (Tq,), dtype=torch.int32, device=cuda)
+    pc.q_pos[:] = seeded_positions(Tq, 900, 906, cuda)
     run_retain_case(esp, pc, 6)
 
 
