@@ -83,6 +83,21 @@ def test_host_side_argument_errors(lib):
         == lib.ESP_ERR_WORKSPACE
     assert "built-in block" in lib.last_error()
     assert L.esp_partial_attn_decode_static(one, one, one, 8, one, one, 0, 0, 0, 4, 4, 128, f, one, one, nul) == lib.ESP_OK
+    # decode combined with the peers' partials: the same checks, the number of peers, null or overlapping arrays
+    def decode_merge(n_peers, peer_O=one, peer_L=one, O=one, LSE=one, Hq=4, D=128, ws=one, ws_bytes=1 << 20):
+        return L.esp_partial_attn_decode_merge(one, one, one, 8, one, one, 2, 10, 5, Hq, 4, D, f, peer_O, peer_L, n_peers,
+                                               O, LSE, ws, ws_bytes, nul)
+    far = (ctypes.c_void_p * 2)(1 << 20, 2 << 20)
+    assert decode_merge(-1) == lib.ESP_ERR_INVALID_ARG
+    assert decode_merge(16) == lib.ESP_ERR_INVALID_ARG and "n_peers=16" in lib.last_error()
+    assert decode_merge(2, far, far, Hq=6) == lib.ESP_ERR_INVALID_ARG
+    assert decode_merge(2, far, far, D=64) == lib.ESP_ERR_UNSUPPORTED
+    assert decode_merge(2, nul, far) == lib.ESP_ERR_INVALID_ARG
+    assert decode_merge(2, (ctypes.c_void_p * 2)(1 << 20, 0), far) == lib.ESP_ERR_INVALID_ARG          # a null partial
+    assert decode_merge(2, far, far, O=ctypes.c_void_p((2 << 20) + 512)) == lib.ESP_ERR_INVALID_ARG     # O inside a peer's O
+    assert "overlaps" in lib.last_error()
+    assert decode_merge(2, far, far, LSE=ctypes.c_void_p((1 << 20) + 4)) == lib.ESP_ERR_INVALID_ARG
+    assert decode_merge(2, far, far, ws=nul, ws_bytes=0) == lib.ESP_ERR_WORKSPACE
     # prefill
     args = dict(batch=1, Tq=16, Tkv=16, max_q=16, max_kv=16, Hq=4, Hkv=4, D=128)
 
@@ -98,6 +113,19 @@ def test_host_side_argument_errors(lib):
     assert prefill(ws_bytes=8) == lib.ESP_ERR_WORKSPACE
     assert prefill(ws=ctypes.c_void_p(8)) == lib.ESP_ERR_WORKSPACE  # misaligned
     assert prefill(Tq=0, max_q=0) == lib.ESP_OK                     # nothing to do
+
+    def prefill_direct(slots=one, num_slots=64, ws=one, ws_bytes=1 << 20, **kw):
+        a = dict(args, **kw)
+        return L.esp_partial_attn_prefill_pool_direct(one, one, one, num_slots, slots, one, one, nul, nul, a["batch"], a["Tq"],
+                                                      a["Tkv"], a["max_q"], a["max_kv"], a["Hq"], a["Hkv"], a["D"], f, 1, 0,
+                                                      one, one, ws, ws_bytes, nul)
+    assert prefill_direct(slots=nul) == lib.ESP_ERR_INVALID_ARG
+    assert prefill_direct(num_slots=0) == lib.ESP_ERR_INVALID_ARG
+    assert prefill_direct(num_slots=-1) == lib.ESP_ERR_INVALID_ARG
+    assert prefill_direct(D=64) == lib.ESP_ERR_UNSUPPORTED
+    assert prefill_direct(Hq=6) == lib.ESP_ERR_INVALID_ARG
+    assert prefill_direct(ws=nul, ws_bytes=0) == lib.ESP_ERR_WORKSPACE
+    assert prefill_direct(Tq=0, max_q=0) == lib.ESP_OK
 
 
 def test_no_oracle_or_fallback_in_product():
