@@ -58,19 +58,22 @@ struct DecodeGeom {
 };
 
 // Head counts of the row-burst kernel: whole 1 KiB head blocks (4 KV heads) that split the 8 wavefronts evenly,
-// and a query group that fits the registers.  Everything else goes to the per-head kernel below.
+// and up to 4 query heads per KV head (from 8 on the dot products outgrow the vector ALU: measured 46 % of the
+// HBM rate at 8, against 51 - 55 % with the group on the matrix cores).  Of the rest, groups of 4 and more query
+// heads go to the matrix-core kernel (decode_gq.hip), groups of 1 to 3 to the per-head kernel below.
 static bool decode_burst_layout(int32_t Hq, int32_t Hkv) {
     const int G = Hq / Hkv;
-    return (Hkv == 4 || Hkv == 8 || Hkv == 16 || Hkv % 32 == 0) && (G == 1 || G == 2 || G == 4 || G == 8);
+    return (Hkv == 4 || Hkv == 8 || Hkv == 16 || Hkv % 32 == 0) && (G == 1 || G == 2 || G == 4);
 }
-// query heads of a KV head handled together by the per-head kernel: the largest of 8, 4, 2, 1 that divides the group
-static int decode_any_chunk(int G) { return G % 8 == 0 ? 8 : G % 4 == 0 ? 4 : G % 2 == 0 ? 2 : 1; }
+// query heads of a KV head handled together by the per-head kernel (groups of 1, 2 or 3 reach it)
+static int decode_any_chunk(int G) { return G % 2 == 0 ? 2 : 1; }
 
 static DecodeGeom decode_geom(int32_t total_tokens, int32_t Hq, int32_t Hkv) {
     DecodeGeom g;
     if (!decode_burst_layout(Hq, Hkv)) {
-        // per-head kernel: every wavefront of a workgroup works on the same KV head, 4 tokens per load and
-        // kDecTB loads per step, the 8 wavefronts on interleaved tokens
+        // per-head and matrix-core kernels: every wavefront of a workgroup works on the same KV head.  The range is
+        // a multiple of what the 8 wavefronts of either kernel consume per step (per-head: 4 tokens per load and
+        // kDecTB loads, on interleaved tokens; matrix cores: a tile of 32 tokens each)
         g.nhb_wg = 0;
         g.nt = kDecWaves;
         g.ygroups = Hkv;
@@ -240,8 +243,8 @@ __global__ __launch_bounds__(kDecWaves * 64) void decode_partial_kernel(
 }
 
 
-// The same partials for any head counts (MQA and GQA with 1, 2, 3, 5, ... KV heads, query groups of any size): one
-// workgroup per (token range, KV head, chunk of GC query heads of that KV head).  A pool row holds only 256 bytes of
+// The same partials for KV head counts off the row-burst layouts with 1 to 3 query heads per KV head (larger groups
+// run on the matrix cores, decode_gq.hip): one workgroup per (token range, KV head, chunk of GC query heads of it).  A pool row holds only 256 bytes of
 // one KV head, so a wavefront's load covers FOUR tokens (16 lanes x 16 bytes each), every 16-lane group keeps the
 // online-softmax state of its own tokens, and the four groups are combined when a request's segment ends.  Partial
 // slots as above, with the 8 wavefronts as the token interleave.  Less bandwidth per instruction than the row-burst
@@ -483,7 +486,12 @@ esp_status launch_decode(const void* q, const void* k_pool, const void* v_pool, 
     float* part_acc = (float*)workspace;
     float* part_ml = part_acc + n * kHeadDim;
     const int G = Hq / Hkv;
-    if (total_tokens > 0 && g.nhb_wg == 0) {
+    if (total_tokens > 0 && g.nhb_wg == 0 && G >= kDecGqMinGroup) {
+        // several query heads per KV head, off the row-burst layouts: the heads of a group as columns of an MFMA tile
+        esp_status st = launch_decode_gq(q, k_pool, v_pool, slot_idx, seq_offsets, B, total_tokens, g.range, g.nwg, Hq, Hkv,
+                                         softmax_scale * kLog2e, part_acc, part_ml, stream);
+        if (st != ESP_OK) return st;
+    } else if (total_tokens > 0 && g.nhb_wg == 0) {
         const int GC = decode_any_chunk(G);
         dim3 grid(g.nwg, Hkv, G / GC), block(kDecWaves * 64);
         const float sl2 = softmax_scale * kLog2e;
@@ -492,12 +500,8 @@ esp_status launch_decode(const void* q, const void* k_pool, const void* v_pool, 
     hipLaunchKernelGGL(decode_partial_any_kernel<GG>, grid, block, 0, stream, (const uint16_t*)q,               \
                        (const uint4*)k_pool, (const uint4*)v_pool, slot_idx, seq_offsets, B, total_tokens,      \
                        g.range, Hq, Hkv, sl2, part_acc, part_ml)
-        switch (GC) {
-            case 1: ESP_DECODE_ANY(1); break;
-            case 2: ESP_DECODE_ANY(2); break;
-            case 4: ESP_DECODE_ANY(4); break;
-            default: ESP_DECODE_ANY(8); break;
-        }
+        if (GC == 2) ESP_DECODE_ANY(2);
+        else ESP_DECODE_ANY(1);
 #undef ESP_DECODE_ANY
         esp_status st = check_launch("decode_partial_any_kernel");
         if (st != ESP_OK) return st;
@@ -512,7 +516,6 @@ esp_status launch_decode(const void* q, const void* k_pool, const void* v_pool, 
             case 1: ESP_DECODE_LAUNCH(1); break;
             case 2: ESP_DECODE_LAUNCH(2); break;
             case 4: ESP_DECODE_LAUNCH(4); break;
-            case 8: ESP_DECODE_LAUNCH(8); break;
             default: return fail(ESP_ERR_UNSUPPORTED, "decode: Hq/Hkv=%d unsupported", G);
         }
 #undef ESP_DECODE_LAUNCH
