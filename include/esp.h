@@ -134,11 +134,10 @@ esp_status esp_partial_attn_prefill_f32(
  *   O [B,Hq,D] bf16, LSE [B,Hq] float.
  *   workspace: at least esp_decode_workspace_bytes(...) bytes, 256-byte aligned.
  * Every Hq that is a multiple of Hkv is accepted (MHA, GQA, MQA).  With 4, 8, 16 or
- * a multiple of 32 KV heads and 1, 2 or 4 query heads per KV head a pool row is
- * read in whole-row bursts and multiplied on the vector ALU; other head counts are
- * read one KV head (256 bytes of a row) at a time, and groups of 4 and more query
- * heads per KV head (8 and more on the layouts above) are multiplied on the matrix
- * cores, the heads of a group as the columns of a tile.
+ * a multiple of 32 KV heads and 1 or 2 query heads per KV head a pool row is read
+ * in whole-row bursts and multiplied on the vector ALU; every other layout is read
+ * one KV head (256 bytes of a row) at a time and multiplied on the matrix cores,
+ * the query heads of a KV head as the columns of a tile.
  */
 esp_status esp_partial_attn_decode(
     const void* q, const void* k_pool, const void* v_pool, int64_t num_slots,

@@ -57,29 +57,28 @@ struct DecodeGeom {
     int32_t ygroups;    // workgroups along y when a row has more than 8 head blocks
 };
 
-// Head counts of the row-burst kernel: whole 1 KiB head blocks (4 KV heads) that split the 8 wavefronts evenly,
-// and up to 4 query heads per KV head (from 8 on the dot products outgrow the vector ALU: measured 46 % of the
-// HBM rate at 8, against 51 - 55 % with the group on the matrix cores).  Of the rest, groups of 4 and more query
-// heads go to the matrix-core kernel (decode_gq.hip), groups of 1 to 3 to the per-head kernel below.
+// Head counts of the row-burst kernel: whole 1 KiB head blocks (4 KV heads) that split the 8 wavefronts evenly, and
+// one or two query heads per KV head.  Everything else (other KV head counts, larger query groups) goes to the
+// matrix-core kernel of decode_gq.hip, which gathers one KV head's 256 bytes of a row at a time but does not pay for
+// the size of the group: measured against it, this kernel's dot products on the vector ALU fall behind from four
+// query heads per KV head on (16/4: 59 % of the HBM rate here, 71 % there; 64/8: 46 % and 68 %), and lead with one
+// or two (32/32: 74 % and 69 %; 32/16: 68 % and 65 %).
 static bool decode_burst_layout(int32_t Hq, int32_t Hkv) {
     const int G = Hq / Hkv;
-    return (Hkv == 4 || Hkv == 8 || Hkv == 16 || Hkv % 32 == 0) && (G == 1 || G == 2 || G == 4);
+    return (Hkv == 4 || Hkv == 8 || Hkv == 16 || Hkv % 32 == 0) && (G == 1 || G == 2);
 }
-// query heads of a KV head handled together by the per-head kernel (groups of 1, 2 or 3 reach it)
-static int decode_any_chunk(int G) { return G % 2 == 0 ? 2 : 1; }
 
 static DecodeGeom decode_geom(int32_t total_tokens, int32_t Hq, int32_t Hkv) {
     DecodeGeom g;
     if (!decode_burst_layout(Hq, Hkv)) {
-        // per-head and matrix-core kernels: every wavefront of a workgroup works on the same KV head.  The range is
-        // a multiple of what the 8 wavefronts of either kernel consume per step (per-head: 4 tokens per load and
-        // kDecTB loads, on interleaved tokens; matrix cores: a tile of 32 tokens each)
+        // matrix-core kernel: every wavefront of a workgroup works on the same KV head, a tile of 32 tokens each per
+        // step; the workgroup combines its wavefronts itself, so there is one partial per (range + request, head)
         g.nhb_wg = 0;
-        g.nt = kDecWaves;
+        g.nt = 1;
         g.ygroups = Hkv;
-        int64_t step = (int64_t)kDecWaves * kDecTB * 4;
+        int64_t step = (int64_t)kDecWaves * 32;
         int64_t want = ((int64_t)total_tokens + kDecMaxWG - 1) / kDecMaxWG;
-        if (want < 4 * step) want = 4 * step;
+        if (want < 2 * step) want = 2 * step;
         want = (want + step - 1) / step * step;
         g.range = (int32_t)want;
         g.nwg = (int32_t)(((int64_t)total_tokens + want - 1) / want);
@@ -243,145 +242,6 @@ __global__ __launch_bounds__(kDecWaves * 64) void decode_partial_kernel(
 }
 
 
-// The same partials for KV head counts off the row-burst layouts with 1 to 3 query heads per KV head (larger groups
-// run on the matrix cores, decode_gq.hip): one workgroup per (token range, KV head, chunk of GC query heads of it).  A pool row holds only 256 bytes of
-// one KV head, so a wavefront's load covers FOUR tokens (16 lanes x 16 bytes each), every 16-lane group keeps the
-// online-softmax state of its own tokens, and the four groups are combined when a request's segment ends.  Partial
-// slots as above, with the 8 wavefronts as the token interleave.  Less bandwidth per instruction than the row-burst
-// kernel (256-byte pieces instead of whole rows), which is why that one is kept for the shapes it covers.
-template <int GC>
-__global__ __launch_bounds__(kDecWaves * 64) void decode_partial_any_kernel(
-    const uint16_t* __restrict__ q, const uint4* __restrict__ k_pool, const uint4* __restrict__ v_pool,
-    const int32_t* __restrict__ slot_idx, const int32_t* __restrict__ seq_offsets, int32_t B, int32_t total_tokens,
-    int32_t range, int32_t Hq, int32_t Hkv, float scale_log2, float* __restrict__ part_acc,
-    float* __restrict__ part_ml) {
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int grp = lane >> 4;                                  // which of the load's four tokens
-    const int dseg = (lane & 15) * 8;
-    const int kvh = blockIdx.y;
-    const int G = Hq / Hkv;
-    const int h0 = kvh * G + blockIdx.z * GC;                   // first query head of this chunk
-    const int w = blockIdx.x;
-    const int64_t row_chunks = (int64_t)Hkv * (kHeadDim * 2 / 16);
-    const int lane_chunk = kvh * (kHeadDim * 2 / 16) + (lane & 15);
-
-    int32_t t0 = w * range;
-    const int32_t t1 = min(t0 + range, total_tokens);
-    if (t0 >= t1) return;
-    int lo = 0, hi = B;   // invariant: seq_offsets[lo] <= t0 < seq_offsets[hi]
-    while (hi - lo > 1) {
-        int mid = (lo + hi) >> 1;
-        if (seq_offsets[mid] <= t0) lo = mid; else hi = mid;
-    }
-    int b = lo;
-
-    while (t0 < t1) {
-        int32_t req_end = seq_offsets[b + 1];
-        if (req_end <= t0) { ++b; continue; }                   // empty request
-        const int32_t pe = min(t1, req_end);
-
-        float qf[GC][8];
-#pragma unroll
-        for (int gi = 0; gi < GC; ++gi) {
-            uint4 qw = *(const uint4*)(q + ((int64_t)b * Hq + h0 + gi) * kHeadDim + dseg);
-            unpack8(qw, qf[gi]);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) qf[gi][e] *= scale_log2;
-        }
-        float m[GC], l[GC], acc[GC][8];
-#pragma unroll
-        for (int gi = 0; gi < GC; ++gi) {
-            m[gi] = -INFINITY; l[gi] = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[gi][e] = 0.f;
-        }
-
-        // token of (step base, load u, wavefront, lane group) = base + 32 u + 4 wave + grp
-        for (int32_t base = t0; base < pe; base += kDecWaves * kDecTB * 4) {
-            uint4 kw[kDecTB], vw[kDecTB];
-            bool valid[kDecTB];
-#pragma unroll
-            for (int u = 0; u < kDecTB; ++u) {
-                const int32_t tok = base + u * (kDecWaves * 4) + wave * 4 + grp;
-                valid[u] = tok < pe;
-                const int32_t slot = slot_idx[valid[u] ? tok : t0];
-                const int64_t off = (int64_t)slot * row_chunks + lane_chunk;
-                kw[u] = k_pool[off];
-                vw[u] = v_pool[off];
-            }
-            float s[kDecTB][GC];
-#pragma unroll
-            for (int u = 0; u < kDecTB; ++u) {
-                float kf[8];
-                unpack8(kw[u], kf);
-#pragma unroll
-                for (int gi = 0; gi < GC; ++gi) {
-                    float d = 0.f;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) d = fmaf(qf[gi][e], kf[e], d);
-                    d = row16_sum(d);
-                    s[u][gi] = valid[u] ? d : -INFINITY;
-                }
-            }
-#pragma unroll
-            for (int gi = 0; gi < GC; ++gi) {
-                float mx = m[gi];
-#pragma unroll
-                for (int u = 0; u < kDecTB; ++u) mx = fmaxf(mx, s[u][gi]);
-                // a lane group may still be without any token: nothing to rescale, nothing to add
-                const float alpha = (mx == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m[gi] - mx);
-                m[gi] = mx;
-                l[gi] *= alpha;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc[gi][e] *= alpha;
-#pragma unroll
-                for (int u = 0; u < kDecTB; ++u) s[u][gi] = valid[u] ? __builtin_amdgcn_exp2f(s[u][gi] - mx) : 0.f;
-            }
-#pragma unroll
-            for (int u = 0; u < kDecTB; ++u) {
-                float vf[8];
-                unpack8(vw[u], vf);
-#pragma unroll
-                for (int gi = 0; gi < GC; ++gi) {
-                    l[gi] += s[u][gi];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[gi][e] = fmaf(s[u][gi], vf[e], acc[gi][e]);
-                }
-            }
-        }
-
-        // the four lane groups hold different tokens: combine them (butterfly over lane bits 4 and 5)
-#pragma unroll
-        for (int gi = 0; gi < GC; ++gi) {
-#pragma unroll
-            for (int sh = 16; sh <= 32; sh <<= 1) {
-                const float mo = __shfl_xor(m[gi], sh), lo2 = __shfl_xor(l[gi], sh);
-                const float mx = fmaxf(m[gi], mo);
-                const float ca = (mx == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m[gi] - mx);
-                const float cb = (mx == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mo - mx);
-                l[gi] = l[gi] * ca + lo2 * cb;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc[gi][e] = acc[gi][e] * ca + __shfl_xor(acc[gi][e], sh) * cb;
-                m[gi] = mx;
-            }
-        }
-        if (grp == 0) {
-            const int64_t pslot = ((int64_t)(w + b) * kDecWaves + wave) * Hq;
-#pragma unroll
-            for (int gi = 0; gi < GC; ++gi) {
-                const int64_t ph = pslot + h0 + gi;
-                float4* dst = (float4*)(part_acc + ph * kHeadDim + dseg);
-                dst[0] = make_float4(acc[gi][0], acc[gi][1], acc[gi][2], acc[gi][3]);
-                dst[1] = make_float4(acc[gi][4], acc[gi][5], acc[gi][6], acc[gi][7]);
-                if (lane == 0) *(float2*)(part_ml + ph * 2) = make_float2(m[gi], l[gi]);
-            }
-        }
-        t0 = pe;
-        ++b;
-    }
-}
-
 // One workgroup per (request, head): 4 groups of 64 lanes split the partials, each lane owns
 // two output elements; the groups are then combined through LDS.
 //
@@ -486,24 +346,9 @@ esp_status launch_decode(const void* q, const void* k_pool, const void* v_pool, 
     float* part_acc = (float*)workspace;
     float* part_ml = part_acc + n * kHeadDim;
     const int G = Hq / Hkv;
-    if (total_tokens > 0 && g.nhb_wg == 0 && G >= kDecGqMinGroup) {
-        // several query heads per KV head, off the row-burst layouts: the heads of a group as columns of an MFMA tile
+    if (total_tokens > 0 && g.nhb_wg == 0) {
         esp_status st = launch_decode_gq(q, k_pool, v_pool, slot_idx, seq_offsets, B, total_tokens, g.range, g.nwg, Hq, Hkv,
                                          softmax_scale * kLog2e, part_acc, part_ml, stream);
-        if (st != ESP_OK) return st;
-    } else if (total_tokens > 0 && g.nhb_wg == 0) {
-        const int GC = decode_any_chunk(G);
-        dim3 grid(g.nwg, Hkv, G / GC), block(kDecWaves * 64);
-        const float sl2 = softmax_scale * kLog2e;
-        if (Hkv > 65535 || G / GC > 65535) return fail(ESP_ERR_UNSUPPORTED, "decode: too many heads for one launch");
-#define ESP_DECODE_ANY(GG)                                                                                      \
-    hipLaunchKernelGGL(decode_partial_any_kernel<GG>, grid, block, 0, stream, (const uint16_t*)q,               \
-                       (const uint4*)k_pool, (const uint4*)v_pool, slot_idx, seq_offsets, B, total_tokens,      \
-                       g.range, Hq, Hkv, sl2, part_acc, part_ml)
-        if (GC == 2) ESP_DECODE_ANY(2);
-        else ESP_DECODE_ANY(1);
-#undef ESP_DECODE_ANY
-        esp_status st = check_launch("decode_partial_any_kernel");
         if (st != ESP_OK) return st;
     } else if (total_tokens > 0) {
         dim3 grid(g.nwg, g.ygroups), block(kDecWaves * 64);
@@ -515,7 +360,6 @@ esp_status launch_decode(const void* q, const void* k_pool, const void* v_pool, 
         switch (G) {
             case 1: ESP_DECODE_LAUNCH(1); break;
             case 2: ESP_DECODE_LAUNCH(2); break;
-            case 4: ESP_DECODE_LAUNCH(4); break;
             default: return fail(ESP_ERR_UNSUPPORTED, "decode: Hq/Hkv=%d unsupported", G);
         }
 #undef ESP_DECODE_LAUNCH

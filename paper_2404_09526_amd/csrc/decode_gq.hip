@@ -1,15 +1,19 @@
-// Decode partial attention for grouped queries on the matrix cores (MQA, GQA with few KV heads; Sec. 2.3 / Sec. 6:
-// the method serves MHA, GQA and MQA alike).  With G query heads per KV head, a resident key row meets G queries:
-// per token 2 * 2 * 128 * G flops on 512 bytes, which the vector ALU cannot keep up with from G = 4 or so on
-// (a per-head kernel on it reaches 11 % of the HBM rate for 32 / 1 heads).  Here the G queries of a request are
-// the 32 columns of an MFMA tile:
+// Decode partial attention on the matrix cores: every head layout but MHA-like ones that the row-burst kernel
+// covers (MQA, GQA with any number of KV heads and query heads per KV head; Sec. 2.3 / Sec. 6: the method serves MHA,
+// GQA and MQA alike).  With G query heads per KV head, a resident key row meets G queries: per token
+// 2 * 2 * 128 * G flops on 512 bytes, which the vector ALU cannot keep up with from G = 4 or so on (a per-head kernel
+// on it reached 11 % of the HBM rate for 32 / 1 heads, the row-burst kernel 46 % for 64 / 8), but which is a dense
+// contraction.  The query heads of a request's KV head are the 32 columns of an MFMA tile (unused columns are zero):
 //   S^T [32 keys x 32 heads] = K_tile [32 x 128] Q^T [128 x 32],   O^T [128 x 32 heads] += V_tile^T [128 x 32] P^T [32 x 32]
-// Work is split as in the other decode kernels: the concatenated token list in equal ranges, one workgroup per
+// The products are far from binding (16 MFMAs per 16 KiB gathered), so the kernel's time does not depend on G.
+// Work is split as in the row-burst kernel: the concatenated token list in equal ranges, one workgroup per
 // (range, KV head, chunk of up to 32 query heads); inside it every wavefront works alone, on every 8th tile of 32
-// tokens of a request's part of the range, with an LDS block of its own (no workgroup barrier anywhere): it
+// tokens of a request's part of the range, with an LDS block of its own (no workgroup barrier inside the sweep): it
 // gathers the tile's K and V rows from their pool slots straight into LDS (16-byte pieces, a full address per
-// lane), multiplies, keeps an exact running maximum, and leaves one partial (accumulator, maximum, sum) per
-// (range + request, wavefront, head) for the combine kernel, like the other decode kernels.
+// lane), multiplies and keeps an exact running maximum; when the request's part of the range is done, the eight
+// wavefronts combine their results through LDS and leave one partial (accumulator, maximum, sum) per
+// (range + request, head) for the combine kernel.  (Eight partials per workgroup, one per wavefront, made the combine
+// kernel read 145 MB for 32 / 1 heads and 64 requests: a quarter of the call's time.)
 #include "mfma_tile.h"
 
 namespace esp {
@@ -173,24 +177,50 @@ __global__ __launch_bounds__(kGqWaves * 64) void decode_partial_gq_kernel(
             slots = slots_next;
         }
 
-        // ---- this wavefront's partial of (range + request): O^T accumulated the ROUNDED probabilities, so it is
-        //      brought to the scale of the unrounded sum that goes out with it (the combine kernel divides by that
-        //      sum, and takes the log-sum-exp from it)
+        // ---- the partial of (range + request): O^T accumulated the ROUNDED probabilities, so each wavefront first
+        //      brings it to the scale of its unrounded sum (the combine kernel divides by the sum that travels with
+        //      the partial, and takes the log-sum-exp from it); then the 8 wavefronts' results are combined through
+        //      LDS (their tile blocks are free now): register rho of every lane to row rho of the wavefront's block,
+        //      64 lanes x 4 bytes a row, then maximum and sum; wavefront j combines registers 8j .. 8j+7 of all
+        //      eight and writes them out.  One partial per (range + request, head) leaves the workgroup.
         const float l_tot = half_swap_sum(l), lr_tot = half_swap_sum(l_r);
         const float fix = lr_tot > 0.f ? l_tot / lr_tot : 0.f;
-        if (qi < ng) {
-            const int64_t ph = ((int64_t)(w + b) * kGqWaves + wave) * Hq + h0 + qi;
-            if (l_tot > 0.f) {
+        float* mine = (float*)(smem + wave * kGqWaveBytes);
 #pragma unroll
-                for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < 4; ++db)
 #pragma unroll
-                    for (int bb = 0; bb < 4; ++bb)
-                        *(float4*)(part_acc + ph * kHeadDim + 32 * db + 8 * bb + 4 * hi) =
-                            make_float4(oacc[db][4 * bb + 0] * fix, oacc[db][4 * bb + 1] * fix, oacc[db][4 * bb + 2] * fix,
-                                        oacc[db][4 * bb + 3] * fix);
+            for (int r = 0; r < 16; ++r) mine[(16 * db + r) * 64 + lane] = oacc[db][r] * fix;
+        mine[64 * 64 + lane] = m;
+        mine[65 * 64 + lane] = l_tot;
+        __syncthreads();
+        {
+            float mw[kGqWaves], mx = -INFINITY;
+#pragma unroll
+            for (int u = 0; u < kGqWaves; ++u) {
+                mw[u] = ((const float*)(smem + u * kGqWaveBytes))[64 * 64 + lane];
+                mx = fmaxf(mx, mw[u]);
             }
-            if (hi == 0) *(float2*)(part_ml + ph * 2) = make_float2(m, l_tot);
+            float lsum = 0.f, out[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int u = 0; u < kGqWaves; ++u) {
+                const float* blk = (const float*)(smem + u * kGqWaveBytes);
+                const float lu = blk[65 * 64 + lane];
+                // a wavefront without a tile of this request (sum 0) has nothing to add
+                const float c = lu > 0.f ? __builtin_amdgcn_exp2f(mw[u] - mx) : 0.f;
+                lsum += lu * c;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) out[e] += blk[(8 * wave + e) * 64 + lane] * c;
+            }
+            if (qi < ng) {
+                const int64_t ph = (int64_t)(w + b) * Hq + h0 + qi;
+                // registers 8 wave .. 8 wave + 7 = block db = wave / 2, r = 8 (wave % 2) .. + 7: two runs of four rows
+                float* dst = part_acc + ph * kHeadDim + 32 * (wave >> 1) + 16 * (wave & 1) + 4 * hi;
+                *(float4*)(dst) = make_float4(out[0], out[1], out[2], out[3]);
+                *(float4*)(dst + 8) = make_float4(out[4], out[5], out[6], out[7]);
+                if (wave == 0 && hi == 0) *(float2*)(part_ml + ph * 2) = make_float2(mx, lsum);
+            }
         }
+        __syncthreads();                                        // the blocks are read: the next request may gather into them
         t0 = pe;
         ++b;
     }

@@ -56,8 +56,7 @@ esp_status launch_decode(const void* q, const void* k_pool, const void* v_pool, 
                          float softmax_scale, void* O, float* LSE, void* workspace, size_t workspace_bytes,
                          hipStream_t stream, const MergeArgs* peers = nullptr, int32_t n_peers = 0);
 
-// the partial kernel for grouped queries on the matrix cores (decode_gq.hip); same partial layout as the per-head kernel
-constexpr int kDecGqMinGroup = 4;   // query heads per KV head from which it is used, where the row-burst kernel does not apply
+// the partial kernel on the matrix cores (decode_gq.hip): one partial per (range + request, head)
 esp_status launch_decode_gq(const void* q, const void* k_pool, const void* v_pool, const int32_t* slot_idx,
                             const int32_t* seq_offsets, int32_t B, int32_t total_tokens, int32_t range, int32_t nwg,
                             int32_t Hq, int32_t Hkv, float scale_log2, float* part_acc, float* part_ml, hipStream_t stream);

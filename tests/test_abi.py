@@ -78,8 +78,8 @@ def test_host_side_argument_errors(lib):
     # decode on the built-in scratch block: the same checks, and sizes beyond the block are refused before any GPU call
     assert L.esp_partial_attn_decode_static(one, one, one, 8, one, one, 2, 10, 5, 6, 4, 128, f, one, one, nul) == lib.ESP_ERR_INVALID_ARG
     assert L.esp_partial_attn_decode_static(one, one, one, 8, one, one, 2, 10, 5, 4, 4, 64, f, one, one, nul) == lib.ESP_ERR_UNSUPPORTED
-    assert lib.esp_decode_workspace_bytes(256, 7_000_000, 1 << 20, 32, 8, 128) > lib.ESP_DECODE_STATIC_SCRATCH_BYTES
-    assert L.esp_partial_attn_decode_static(one, one, one, 1 << 24, one, one, 256, 7_000_000, 1 << 20, 32, 8, 128, f, one, one, nul) \
+    assert lib.esp_decode_workspace_bytes(256, 7_000_000, 1 << 20, 64, 32, 128) > lib.ESP_DECODE_STATIC_SCRATCH_BYTES
+    assert L.esp_partial_attn_decode_static(one, one, one, 1 << 24, one, one, 256, 7_000_000, 1 << 20, 64, 32, 128, f, one, one, nul) \
         == lib.ESP_ERR_WORKSPACE
     assert "built-in block" in lib.last_error()
     assert L.esp_partial_attn_decode_static(one, one, one, 8, one, one, 0, 0, 0, 4, 4, 128, f, one, one, nul) == lib.ESP_OK

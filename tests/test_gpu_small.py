@@ -288,11 +288,10 @@ def test_decode_heads_and_empty_requests(esp, cuda, Hq, Hkv):
 @pytest.mark.parametrize("Hq,Hkv", [(32, 1), (4, 1), (8, 2), (12, 12), (24, 3), (40, 20), (5, 5), (48, 2), (9, 3), (40, 1),
                                     (66, 2), (32, 4), (64, 8), (7, 1)])
 def test_decode_any_head_counts(esp, cuda, Hq, Hkv):
-    """MQA, two KV heads, KV head counts that are no multiple of 4, query groups of every size: the per-head kernel
-    (1 to 3 query heads per KV head) and the matrix-core kernel (4 and more; 40 / 1 and 66 / 2 need a second chunk of
-    columns, 7 / 1 and 66 / 2 leave columns of a tile unused; 32 / 4 and 64 / 8 are row-burst layouts that go there
-    because of their groups of 8).  Empty requests, requests shorter than one load or tile, requests across several
-    token ranges."""
+    """MQA, two KV heads, KV head counts that are no multiple of 4, query groups of every size: all on the matrix-core
+    kernel (40 / 1 and 66 / 2 need a second chunk of columns, 7 / 1, 5 / 5 and 66 / 2 leave columns of a tile unused;
+    32 / 4 and 64 / 8 are row-burst layouts that go there because of their groups of 8).  Empty requests, requests
+    shorter than one tile, requests across several token ranges."""
     lens = [0, 1, 2, 3, 5, 0, 65, 700, 5000, 129, 0]
     dc = wl.decode_pool(f"decode-any-{Hq}/{Hkv}", lens, 8192, Hq, Hkv, 34, cuda, n_new=0)
     O, LSE, kp, vp = run_decode_case(esp, dc)

@@ -59,7 +59,7 @@ def test_decode_on_the_built_in_scratch_block(cuda):
 def test_a_call_beyond_the_block_is_refused(cuda):
     """Sizes whose split-K partials do not fit the block: a clear error, nothing launched (the pointers are never read)."""
     from paper_2404_09526_amd import binding as esp
-    B, total, Hq, Hkv = 256, 7_000_000, 32, 8
+    B, total, Hq, Hkv = 256, 7_000_000, 64, 32
     assert esp.esp_decode_workspace_bytes(B, total, 1 << 20, Hq, Hkv, 128) > esp.ESP_DECODE_STATIC_SCRATCH_BYTES
     one = ctypes.c_void_p(256)
     rc = esp.lib.esp_partial_attn_decode_static(one, one, one, 1 << 24, one, one, B, total, 1 << 20, Hq, Hkv, 128,
