@@ -298,6 +298,36 @@ def test_decode_any_head_counts(esp, cuda, Hq, Hkv):
     assert torch.isneginf(LSE[[0, 5, 10]]).all() and (O[[0, 5, 10]] == 0).all()
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2, 3, 4, 5, 6, 7])
+def test_decode_randomized_layouts(esp, cuda, seed):
+    """Drawn from a seeded generator: head layout (both kernels), number of requests, and a length mix with many
+    requests shorter than a tile (several of them, and empty ones, inside one token range), a few of several thousand
+    tokens (cut by range boundaries) and lengths at and around multiples of 32; then the fused decode + merge of the
+    same case.  Every request and head against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    Hq, Hkv = [(32, 32), (8, 8), (32, 8), (16, 2), (5, 1), (36, 3), (64, 32), (33, 1)][seed]
+    B = int(rng.integers(3, 90))
+    kinds = rng.integers(0, 6, B)
+    lens = np.where(kinds == 0, 0, np.where(kinds <= 2, rng.integers(1, 40, B),
+                    np.where(kinds == 3, 32 * rng.integers(1, 9, B) + rng.integers(-1, 2, B), rng.integers(200, 6000, B))))
+    if lens.sum() == 0:
+        lens[0] = 77
+    dc = wl.decode_pool(f"decode-random-{seed} ({Hq}/{Hkv})", lens.tolist(), 1 << 17, Hq, Hkv, 2000 + seed, cuda, n_new=0)
+    O, LSE, kp, vp = run_decode_case(esp, dc)
+    empty = torch.from_numpy(np.flatnonzero(lens == 0)).to(cuda)
+    assert torch.isneginf(LSE[empty]).all() and (O[empty] == 0).all()
+    Of, Lf = esp.esp_partial_attn_decode_merge(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, int(dc.lens.max()),
+                                               list(dc.peer_O), list(dc.peer_LSE), softmax_scale=dc.scale)
+    torch.cuda.synchronize()
+    off, slots = wl.host_i32(dc.seq_offsets), wl.host_i32(dc.slot_idx)
+    Or, Lr = oracle.partial_attn_decode_all(wl.bits(dc.q), kp, vp, slots, off, dc.scale)
+    Op = np.stack([Or] + [oracle.bf16_bits_to_f64(wl.bits(t)) for t in dc.peer_O])
+    Lp = np.stack([Lr] + [t.cpu().numpy().astype(np.float64) for t in dc.peer_LSE])
+    Oref, Lref = oracle.merge_partials(Op, Lp)
+    check_o_lse(Of.float().cpu().numpy().reshape(-1, dc.D), Lf.cpu().numpy().reshape(-1), Oref.reshape(-1, dc.D), Lref.reshape(-1),
+                f"{dc.name} decode + merge in one call")
+
+
 def test_decode_mqa_many_ranges_and_merge(esp, cuda):
     """MQA 32 / 1 at a size that is cut into many token ranges, then merged with peer partials."""
     lens = wl.lognormal_lengths(16, 6000, 10, 60000, 35)
