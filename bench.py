@@ -437,13 +437,12 @@ def main():
         ml_own, ml_peer = int(lens[:h].max()), int(lens[h:].max())
         q_host = dc.q[h:].cpu().pin_memory()                       # the other masters' queries, as they come off the wire
         q_peer = torch.empty_like(dc.q[h:])
-        O_own, L_own = torch.empty_like(dc.q[:h]), torch.empty((h, dc.Hq), dtype=torch.float32, device=dev)
         O_peer, L_peer = torch.empty_like(dc.q[h:]), torch.empty((dc.B - h, dc.Hq), dtype=torch.float32, device=dev)
         O_back = torch.empty(O_peer.shape, dtype=O_peer.dtype).pin_memory(); L_back = torch.empty(L_peer.shape, dtype=L_peer.dtype).pin_memory()
         ws_own = torch.empty(esp.esp_decode_workspace_bytes(h, off_h, ml_own, dc.Hq, dc.Hkv, dc.D), dtype=torch.uint8, device=dev)
         ws_peer = torch.empty(esp.esp_decode_workspace_bytes(dc.B - h, dc.total_tokens - off_h, ml_peer, dc.Hq, dc.Hkv, dc.D),
                               dtype=torch.uint8, device=dev)
-        mO_own, mL_own = torch.empty_like(O_own), torch.empty_like(L_own)
+        mO_own, mL_own = torch.empty_like(dc.q[:h]), torch.empty((h, dc.Hq), dtype=torch.float32, device=dev)
         wire = torch.cuda.Stream()
 
         def masters():
@@ -451,21 +450,27 @@ def main():
             wire.wait_stream(main)
             with torch.cuda.stream(wire):
                 q_peer.copy_(q_host, non_blocking=True)           # peers' queries arrive while the own requests are decoded
-            esp.esp_partial_attn_decode(dc.q[:h], dc.k_pool, dc.v_pool, own_slots, own_off, ml_own, softmax_scale=dc.scale,
-                                        O=O_own, LSE=L_own, workspace=ws_own)
+            # own requests: local partial attention and the merge with what the peers sent, one call
+            esp.esp_partial_attn_decode_merge(dc.q[:h], dc.k_pool, dc.v_pool, own_slots, own_off, ml_own,
+                                              [p[:h] for p in dc.peer_O], [p[:h] for p in dc.peer_LSE], softmax_scale=dc.scale,
+                                              O=mO_own, LSE=mL_own, workspace=ws_own)
             main.wait_stream(wire)
             esp.esp_partial_attn_decode(q_peer, dc.k_pool, dc.v_pool, peer_slots, peer_off, ml_peer, softmax_scale=dc.scale,
                                         O=O_peer, LSE=L_peer, workspace=ws_peer)
             wire.wait_stream(main)
             with torch.cuda.stream(wire):
                 O_back.copy_(O_peer, non_blocking=True); L_back.copy_(L_peer, non_blocking=True)   # results go back to their masters
-            esp.esp_merge_partials([O_own] + [p[:h] for p in dc.peer_O], [L_own] + [p[:h] for p in dc.peer_LSE], O=mO_own, LSE=mL_own)
             main.wait_stream(wire)
 
         def one_call():
-            esp.esp_partial_attn_decode(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, max_len,
-                                        softmax_scale=dc.scale, O=dO, LSE=dL, workspace=ws_dc)
-            esp.esp_merge_partials([dO] + list(dc.peer_O), [dL] + list(dc.peer_LSE), O=mO, LSE=mL)
+            esp.esp_partial_attn_decode_merge(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, max_len,
+                                              list(dc.peer_O), list(dc.peer_LSE), softmax_scale=dc.scale, O=mO, LSE=mL,
+                                              workspace=ws_dc)
+
+        # the helped requests' partial results, for comparison: one plain call over all requests
+        esp.esp_partial_attn_decode(dc.q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, max_len,
+                                    softmax_scale=dc.scale, O=dO, LSE=dL, workspace=ws_dc)
+        torch.cuda.synchronize()
 
         times = {}
         for fn in (one_call, masters, one_call, masters):
@@ -477,7 +482,7 @@ def main():
             e1.record(); torch.cuda.synchronize()
             times.setdefault(fn.__name__, []).append(e0.elapsed_time(e1) / args.steps)
         t_one, t_mm = min(times["one_call"]), min(times["masters"])
-        diff = max(float((O_own.float() - dO[:h].float()).abs().max()), float((O_peer.float() - dO[h:].float()).abs().max()),
+        diff = max(float((mO_own.float() - mO[:h].float()).abs().max()), float((O_peer.float() - dO[h:].float()).abs().max()),
                    float((O_back.float() - dO[h:].float().cpu()).abs().max()))
         result["multi_master"] = {"ms_one_decode_call": t_one, "ms_two_masters": t_mm, "overhead_pct": 100.0 * (t_mm / t_one - 1.0),
                                   "own_requests": h, "peer_requests": dc.B - h, "query_bytes_in": q_host.numel() * 2,

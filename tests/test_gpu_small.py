@@ -210,6 +210,10 @@ def test_multi_master_decode_on_two_streams(esp, cuda):
         with torch.cuda.stream(wire):
             O_back.copy_(O_peer, non_blocking=True); L_back.copy_(L_peer, non_blocking=True)   # results go back to their masters
         esp.esp_merge_partials([O_own] + [p[:h] for p in dc.peer_O], [L_own] + [p[:h] for p in dc.peer_LSE], O=mO, LSE=mL)
+        # the same master step as ONE call (local attention and merge together), while the copies still run
+        fO, fL = esp.esp_partial_attn_decode_merge(dc.q[:h], dc.k_pool, dc.v_pool, own_slots, own_off, ml_own,
+                                                   [p[:h] for p in dc.peer_O], [p[:h] for p in dc.peer_LSE],
+                                                   softmax_scale=dc.scale, workspace=ws_own)
         main.wait_stream(wire)
         torch.cuda.synchronize()
         check_o_lse(O_own.float().cpu().numpy().reshape(-1, dc.D), L_own.cpu().numpy().reshape(-1), Or[:h].reshape(-1, dc.D),
@@ -222,6 +226,11 @@ def test_multi_master_decode_on_two_streams(esp, cuda):
         Oref, Lref = oracle.merge_partials(Op, Lp)
         check_o_lse(mO.float().cpu().numpy().reshape(-1, dc.D), mL.cpu().numpy().reshape(-1), Oref.reshape(-1, dc.D), Lref.reshape(-1),
                     f"merge at the master, round {rnd}")
+        Op = np.stack([Or[:h]] + [oracle.bf16_bits_to_f64(wl.bits(p[:h].contiguous())) for p in dc.peer_O])
+        Lp = np.stack([Lr[:h]] + [p[:h].cpu().numpy().astype(np.float64) for p in dc.peer_LSE])
+        Oref, Lref = oracle.merge_partials(Op, Lp)
+        check_o_lse(fO.float().cpu().numpy().reshape(-1, dc.D), fL.cpu().numpy().reshape(-1), Oref.reshape(-1, dc.D), Lref.reshape(-1),
+                    f"the master's step as one call, round {rnd}")
 
 
 # ------------------------------------------------------------------ prefill: layouts and edge cases
