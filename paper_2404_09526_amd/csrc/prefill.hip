@@ -109,7 +109,8 @@ constexpr float kSumLimit = 1048576.f;  // 2^20: a tile's probability sum above 
 
 template <int V> struct IC { static constexpr int value = V; };
 
-// RETAIN: the variant that also keeps rows of the shard in the token pool while they pass through LDS (proactive
+// MODE 0: the plain kernel.
+// RETAIN (MODE 1): the variant that also keeps rows of the shard in the token pool while they pass through LDS (proactive
 // scale-down, Sec. 4.1 / Fig. 7).  Every KV tile of a request and KV head is OWNED by one item, which stores its K
 // and V rows to the pool slots that are not negative:
 //   * a request whose shard rows are about as many as its query rows (a striped shard, causal self-attention): the
