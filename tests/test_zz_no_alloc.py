@@ -2,7 +2,7 @@
 library) against the entry point that takes a workspace: same kernels, so the outputs must agree bit for bit, which is
 within the parity bar by construction (the workspace variant is checked against the oracle by the other tests; one case
 here is checked against the oracle as well).  Two calls in a row on the shared block, the second with a smaller input,
-called through the raw C symbols."""
+called through the raw C symbols; and a decode step recorded into a graph and replayed."""
 import ctypes
 
 import numpy as np
@@ -54,6 +54,59 @@ def test_decode_on_the_built_in_scratch_block(cuda):
     Or, Lr = oracle.partial_attn_decode_all(wl.bits(dc.q), kp, vp, slots, off, dc.scale)
     check_o_lse(O_small.float().cpu().numpy().reshape(-1, dc.D), L_small.cpu().numpy().reshape(-1), Or.reshape(-1, dc.D), Lr.reshape(-1),
                 "static-small")
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (32, 8)])
+def test_decode_step_replayed_from_a_captured_graph(cuda, Hq, Hkv):
+    """What the entry point is for: a decode step (append of the new tokens' rows, then decode on the built-in block)
+    recorded into a graph, where nothing may allocate.  The graph is replayed several times with other queries and
+    other new rows in the same buffers, with eager work and host synchronisation in between; every replay is compared
+    bit for bit with the eager calls on the same inputs (append + decode with a workspace).  Both partial kernels."""
+    from paper_2404_09526_amd import binding as esp
+    dc = wl.decode_pool(f"graph-step-{Hq}/{Hkv}", [300, 0, 1500, 64, 9, 2200, 700, 1], 8192, Hq, Hkv, 61, cuda, n_new=6)
+    ml = int(dc.lens.max())
+    gen = torch.Generator(device=cuda).manual_seed(99)
+    ws = torch.empty(esp.esp_decode_workspace_bytes(dc.B, dc.total_tokens, ml, Hq, Hkv, dc.D), dtype=torch.uint8, device=cuda)
+    # the new tokens replace the LAST token's row of the six non-empty requests that have one (their slots are in the
+    # slot list already, so that the decode reads what the append just wrote)
+    off = wl.host_i32(dc.seq_offsets)
+    last = [int(off[b + 1]) - 1 for b in range(dc.B) if off[b + 1] > off[b]][:6]
+    tgt = dc.slot_idx[torch.tensor(last, device=cuda)].contiguous()
+    new_k = wl.randn_bf16((len(last), Hkv, dc.D), gen, cuda); new_v = wl.randn_bf16((len(last), Hkv, dc.D), gen, cuda)
+    q = dc.q.clone()
+    O_g = torch.full_like(q, float("nan")); L_g = torch.full((dc.B, Hq), float("nan"), dtype=torch.float32, device=cuda)
+
+    def step(static):
+        esp.esp_kv_append(new_k, new_v, tgt, dc.k_pool, dc.v_pool)
+        if static:
+            esp.esp_partial_attn_decode_static(q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, ml, softmax_scale=dc.scale, O=O_g, LSE=L_g)
+            return None
+        return esp.esp_partial_attn_decode(q, dc.k_pool, dc.v_pool, dc.slot_idx, dc.seq_offsets, ml, softmax_scale=dc.scale, workspace=ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                                  # warm-up on a side stream (the block's address is looked up here)
+        step(True)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step(True)
+    for rep in range(4):
+        print(f"[case] graph replay {rep} of {dc.name}", flush=True)
+        q.copy_(wl.randn_bf16(tuple(q.shape), gen, cuda))
+        new_k.copy_(wl.randn_bf16(tuple(new_k.shape), gen, cuda)); new_v.copy_(wl.randn_bf16(tuple(new_v.shape), gen, cuda))
+        O_g.fill_(float("nan")); L_g.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        O_e, L_e = step(False)                                     # eager, same inputs (the append rewrites the same rows)
+        torch.cuda.synchronize()
+        assert torch.equal(O_g.view(torch.int16), O_e.view(torch.int16)) and torch.equal(L_g.view(torch.int32), L_e.view(torch.int32)), rep
+        assert torch.isfinite(L_g[[0, 2, 3, 4, 5, 6, 7]]).all() and torch.isneginf(L_g[1]).all()
+        if rep == 0:
+            first = O_g.clone()
+        else:
+            assert not torch.equal(O_g.view(torch.int16), first.view(torch.int16))   # the replay saw the new inputs
 
 
 def test_a_call_beyond_the_block_is_refused(cuda):
