@@ -321,7 +321,10 @@ def main():
     if dc is not None:
         result["decode"] = summ["decode"]
         gbs = summ["decode"]["gbs"]
-        result["roofline_decode"] = {"kernel": "decode_partial_kernel", "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS,
+        # whole pool rows on the vector ALU for MHA-like layouts, one KV head at a time on the matrix cores otherwise
+        burst = dc.Hkv in (4, 8, 16) or dc.Hkv % 32 == 0
+        dkernel = "decode_partial_kernel" if burst and dc.Hq // dc.Hkv <= 2 else "decode_partial_gq_kernel"
+        result["roofline_decode"] = {"kernel": dkernel, "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS,
                                      "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "traffic": None, "launch_ms": summ["decode"]["ms"],
                                      "bytes_per_launch": summ["decode"]["bytes"]}
         result["config"].update({"decode_B": dc.B, "decode_total_tokens": dc.total_tokens, "pool_slots": dc.num_slots})
