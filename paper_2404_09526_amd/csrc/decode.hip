@@ -182,8 +182,8 @@ __global__ __launch_bounds__(kDecWaves * 64) void decode_partial_kernel(
                 valid[u] = tok < pe;
                 int32_t slot = slot_idx[valid[u] ? tok : base];  // uniform per wavefront
                 int64_t off = (int64_t)slot * row_chunks + lane_chunk;
-                kw[u] = k_pool[off];
-                vw[u] = v_pool[off];
+                kw[u] = load_once(&k_pool[off]);
+                vw[u] = load_once(&v_pool[off]);
             }
             float s[kDecTB][G];
 #pragma unroll

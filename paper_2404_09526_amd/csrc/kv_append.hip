@@ -17,8 +17,8 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const uint4* __restrict_
     int32_t slot = slot_idx[t];
     if (slot < 0) return;  // token not retained on this instance
     int64_t dst = (int64_t)slot * chunks_per_row + c;
-    k_pool[dst] = k[i];
-    v_pool[dst] = v[i];
+    k_pool[dst] = load_once(&k[i]);
+    v_pool[dst] = load_once(&v[i]);
 }
 
 // esp_kv_gather: the inverse view, rows of the pool in the order of a slot list (a request's resident K/V as the
@@ -35,8 +35,8 @@ __global__ __launch_bounds__(256) void kv_gather_kernel(const uint4* __restrict_
     uint4 kk = make_uint4(0u, 0u, 0u, 0u), vv = kk;
     if (slot >= 0 && slot < num_slots) {
         int64_t src = (int64_t)slot * chunks_per_row + c;
-        kk = k_pool[src];
-        vv = v_pool[src];
+        kk = load_once(&k_pool[src]);
+        vv = load_once(&v_pool[src]);
     }
     k[i] = kk;
     v[i] = vv;

@@ -36,10 +36,10 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs parts, int32_t P, 
                 float f[8];
                 if (F32) {
                     const float4* src = (const float4*)parts.O_parts[p] + (pair * 16 + seg) * 2;
-                    const float4 a = src[0], b = src[1];
+                    const float4 a = load_once(&src[0]), b = load_once(&src[1]);
                     f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
                 } else {
-                    const uint4 o = ((const uint4*)parts.O_parts[p])[pair * 16 + seg];
+                    const uint4 o = load_once(&((const uint4*)parts.O_parts[p])[pair * 16 + seg]);
                     f[0] = bf16_lo(o.x); f[1] = bf16_hi(o.x); f[2] = bf16_lo(o.y); f[3] = bf16_hi(o.y);
                     f[4] = bf16_lo(o.z); f[5] = bf16_hi(o.z); f[6] = bf16_lo(o.w); f[7] = bf16_hi(o.w);
                 }

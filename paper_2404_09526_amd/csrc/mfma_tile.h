@@ -30,7 +30,6 @@ __device__ __forceinline__ float half_swap_sum(float x) {
 }
 
 #define ESP_GLOBAL __attribute__((address_space(1)))
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // One global -> LDS transfer of 64 x 16 bytes: lane L's 16 bytes (at gbase + voff) land at lds_addr + 16*L.
 // Issued as assembly so that the loads stay in flight across LDS reads of other stages; the matching
@@ -42,6 +41,12 @@ __device__ __forceinline__ void load_to_lds_b128(uint32_t lds_addr, const void* 
 // the same with a full address per lane (rows scattered over a pool larger than a 32-bit offset reaches)
 __device__ __forceinline__ void load_to_lds_b128_at(uint32_t lds_addr, const void* src) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(lds_addr), "v"(src) : "memory", "m0");
+}
+// the same for rows that are read once (a decode pass over the pool): marked non-temporal, so that they do not
+// displace what the caches hold
+__device__ __forceinline__ void load_to_lds_b128_at_nt(uint32_t lds_addr, const void* src) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt"
                  :: "s"(lds_addr), "v"(src) : "memory", "m0");
 }
 __device__ __forceinline__ void load_to_lds_b32(uint32_t lds_addr, const void* gbase, uint32_t voff) {
