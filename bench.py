@@ -277,8 +277,8 @@ def summarize(recs, pc, dc):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1. "
-              "DESIGN.md describes how the path would shard.", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding): the figure it reports is one GPU's "
+              "throughput on its share of the sequence-parallel work; use --gpus 1.", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch
