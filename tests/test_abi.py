@@ -42,7 +42,7 @@ def test_workspace_queries(lib):
     a = lib.esp_decode_workspace_bytes(64, 860000, 131072, 32, 32, 128)
     assert 0 < a < 64 << 20
     assert lib.esp_decode_workspace_bytes(64, 860000, 131072, 32, 5, 128) == 0     # Hq % Hkv != 0: the call is refused
-    for Hq, Hkv in [(32, 1), (8, 2), (12, 12), (24, 3), (40, 20)]:                # head counts of the per-head kernel
+    for Hq, Hkv in [(32, 1), (8, 2), (12, 12), (24, 3), (40, 20)]:                # head counts of the matrix-core kernel
         assert 0 < lib.esp_decode_workspace_bytes(64, 860000, 131072, Hq, Hkv, 128) < 512 << 20
 
 
