@@ -140,8 +140,6 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillArgs a) {
                   kLdsFlag = kLdsSched + kPfWaves * 64 * 8, kLdsSlot = kLdsFlag + 16,
                   kLdsTotal = kLdsSlot + (RETAIN ? 8 * kBN * 4 : POOL ? kStages * kBN * 4 : 0);
     __shared__ __attribute__((aligned(1024))) unsigned char smem[kLdsTotal];
-    unsigned char (*lds_k)[kKTileBytes] = (unsigned char (*)[kKTileBytes])(smem + kLdsK);
-    unsigned char (*lds_v)[kTileBytes] = (unsigned char (*)[kTileBytes])(smem + kLdsV);
     int32_t (*lds_pos)[kBN] = (int32_t (*)[kBN])(smem + kLdsPos);
     int32_t (*lds_qmm)[kPfWaves] = (int32_t (*)[kPfWaves])(smem + kLdsQmm);
 
